@@ -1,0 +1,57 @@
+// Host-side launchers of the HIP kernels (each enqueues on the given stream and returns).
+#pragma once
+#include "common.h"
+
+// ---- bf16 path (kernels_bf16.hip)
+void launch_pack_weight(const void *src, void *dst, int N, int K, hipStream_t st);
+void launch_kv_import_bf16(const void *k, const void *v, void *kc, void *vc, int H, int len, int dh,
+                           int max_seq, hipStream_t st);
+void launch_gemm_bf16(const GemmArgs &a, hipStream_t st);
+void launch_attn_bf16(const AttnArgs &a, hipStream_t st);
+
+// ---- fp32 path (kernels_f32.hip)
+void launch_kv_import_f32(const void *k, const void *v, void *kc, void *vc, int H, int len, int dh,
+                          int max_seq, hipStream_t st);
+void launch_gemm_f32(const GemmArgs &a, hipStream_t st);
+void launch_attn_f32(const AttnArgs &a, hipStream_t st);
+
+// ---- shared small kernels (kernels_misc.hip)
+struct StepState {            // device pointers describing the rows of the step in flight
+    int *row_tok, *row_pos, *row_slot;   // [R]
+    int *T, *pending;                    // [max_batch]
+    int *batch_slots;                    // [n_seqs]
+    int *keff;                           // [n_seqs] drafts actually used per sequence
+    int *draft;                          // [n_seqs][max_k]
+    int *nacc, *next, *emit;             // results: [n_seqs], [n_seqs], [n_seqs][max_k+1]
+    int *otok;                           // [R] arg max per row
+};
+struct GenState {             // device-resident state of llma_generate
+    int *y; int *n_out; int *n_steps; int *trace;  // y[max_new], trace[max_new][4]
+    int *cur;                            // [2] (doc, pos) of the trigger of the step in flight
+    const int *ref; const int *doc_offsets; const int *ref_doc; int ref_len, n_docs;
+    int n, k, max_new;
+    const int *prompt;                   // device copy of the prompt (prefill)
+};
+
+// rows of a verify step: row (b, j) = pending[slot_b] (j = 0) or draft[b][j-1]; pos = T[slot_b] + j
+void launch_setup_step_rows(const StepState &s, int n_seqs, int m, int max_k, hipStream_t st);
+// rows of a prefill chunk for one slot: tokens prompt[off .. off+m), pos = T[slot] + j
+void launch_setup_prefill_rows(const StepState &s, const int *prompt_dev, int off, int m, int slot, hipStream_t st);
+void launch_advance_T(const StepState &s, int slot, int by, hipStream_t st);
+// h[r][:] = embed[row_tok[r]][:]  (embed bf16 or fp32 -> fp32)
+void launch_embed(const void *embed, int is_bf16, const int *row_tok, float *h, int R, int d, hipStream_t st);
+// x = RMSNorm(h; g): bf16 hi/lo (is_bf16) or fp32 into out_hi
+void launch_rmsnorm(const float *h, const float *g, float eps, void *out_hi, void *out_lo, int is_bf16,
+                    int R, int d, hipStream_t st);
+// rotate q, k of every row at its position, write q, append k and v to the cache
+void launch_rope_kv(const float *qkv, const StepState &s, const float *cs_table, void *q_out, void *kc, void *vc,
+                    int is_bf16, int R, int H, int dh, int max_seq, hipStream_t st);
+// final arg max over the per-row partials, then prefix accept + KV truncate + bookkeeping
+void launch_argmax_accept(const float *pval, const int *pidx, int n_part, const StepState &s, int n_seqs, int m,
+                          int max_k, const GenState *gen /*device copy or null*/, hipStream_t st);
+// trigger scan for the sequence being generated; fills keff[0] / draft[0][:]
+void launch_trigger(const GenState *gen_dev, const StepState &s, int max_k, hipStream_t st);
+// stateless trigger on device arrays (llma_find_trigger): result[0..2] = matched, doc, pos
+void launch_trigger_plain(const int *y, int y_len, const int *ref, const int *doc_offsets, const int *ref_doc,
+                          int ref_len, int n, int *result, hipStream_t st);
+void launch_fill_ref_doc(const int *doc_offsets, int n_docs, int *ref_doc, int ref_len, hipStream_t st);

@@ -1,0 +1,286 @@
+// Small kernels around the GEMMs and attention: row set-up, embedding gather, RMSNorm,
+// RoPE + KV append, the vocabulary arg max with the prefix-accept / KV-truncate decision
+// (paper: Algorithm 1, the compare loop after the verification forward), and the n-gram
+// trigger scan over the reference (paper: Method, the match that starts a copy).
+#include "common.h"
+#include "kernels.h"
+
+// ---------------------------------------------------------------------------------------------
+// row set-up
+// ---------------------------------------------------------------------------------------------
+__global__ void setup_step_rows_kernel(StepState s, int n_seqs, int m, int max_k) {
+    int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= n_seqs * m) return;
+    int b = idx / m, j = idx % m;
+    int slot = s.batch_slots[b];
+    int tok;
+    if (j == 0) tok = s.pending[slot];
+    else tok = (j - 1 < s.keff[b]) ? s.draft[b * max_k + j - 1] : 0;   // rows past keff are padding
+    s.row_tok[idx] = tok;
+    s.row_pos[idx] = s.T[slot] + j;
+    s.row_slot[idx] = slot;
+}
+void launch_setup_step_rows(const StepState &s, int n_seqs, int m, int max_k, hipStream_t st) {
+    int R = n_seqs * m;
+    hipLaunchKernelGGL(setup_step_rows_kernel, dim3((R + 63) / 64), dim3(64), 0, st, s, n_seqs, m, max_k);
+}
+
+__global__ void setup_prefill_rows_kernel(StepState s, const int *prompt, int off, int m, int slot) {
+    int j = threadIdx.x;
+    if (j >= m) return;
+    s.row_tok[j] = prompt[off + j];
+    s.row_pos[j] = s.T[slot] + j;
+    s.row_slot[j] = slot;
+    if (j == 0) s.batch_slots[0] = slot;
+}
+void launch_setup_prefill_rows(const StepState &s, const int *prompt_dev, int off, int m, int slot, hipStream_t st) {
+    hipLaunchKernelGGL(setup_prefill_rows_kernel, dim3(1), dim3(64), 0, st, s, prompt_dev, off, m, slot);
+}
+
+__global__ void advance_T_kernel(StepState s, int slot, int by) { s.T[slot] += by; }
+void launch_advance_T(const StepState &s, int slot, int by, hipStream_t st) {
+    hipLaunchKernelGGL(advance_T_kernel, dim3(1), dim3(1), 0, st, s, slot, by);
+}
+
+// ---------------------------------------------------------------------------------------------
+// embedding gather
+// ---------------------------------------------------------------------------------------------
+__global__ void embed_kernel(const void *embed, int is_bf16, const int *row_tok, float *h, int d) {
+    int r = blockIdx.x;
+    size_t base = (size_t)row_tok[r] * d;
+    for (int c = threadIdx.x; c < d; c += blockDim.x)
+        h[(size_t)r * d + c] = is_bf16 ? bf16_to_f32(((const bf16_t *)embed)[base + c]) : ((const float *)embed)[base + c];
+}
+void launch_embed(const void *embed, int is_bf16, const int *row_tok, float *h, int R, int d, hipStream_t st) {
+    hipLaunchKernelGGL(embed_kernel, dim3(R), dim3(256), 0, st, embed, is_bf16, row_tok, h, d);
+}
+
+// ---------------------------------------------------------------------------------------------
+// RMSNorm: one workgroup per row; fixed summation order (thread-strided, butterfly, wave order)
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float *__restrict__ h, const float *__restrict__ g, float eps,
+                                                      void *out_hi, void *out_lo, int is_bf16, int d) {
+    __shared__ float part[4];
+    const int r = blockIdx.x;
+    const float *x = h + (size_t)r * d;
+    float ss = 0.f;
+    for (int c = threadIdx.x; c < d; c += 256) ss += x[c] * x[c];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    float tot = ((part[0] + part[1]) + part[2]) + part[3];
+    float rstd = 1.0f / sqrtf(tot / (float)d + eps);
+    for (int c = threadIdx.x; c < d; c += 256) {
+        float v = x[c] * rstd * g[c];
+        if (is_bf16) {
+            bf16_t hi, lo;
+            split_bf16(v, hi, lo);
+            ((bf16_t *)out_hi)[(size_t)r * d + c] = hi;
+            ((bf16_t *)out_lo)[(size_t)r * d + c] = lo;
+        } else {
+            ((float *)out_hi)[(size_t)r * d + c] = v;
+        }
+    }
+}
+void launch_rmsnorm(const float *h, const float *g, float eps, void *out_hi, void *out_lo, int is_bf16,
+                    int R, int d, hipStream_t st) {
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3(R), dim3(256), 0, st, h, g, eps, out_hi, out_lo, is_bf16, d);
+}
+
+// ---------------------------------------------------------------------------------------------
+// RoPE + KV append.  grid (rows, heads), head_dim/2 threads: thread i rotates the pair
+// (i, i + head_dim/2) of q and k by angle pos * theta^(-2i/head_dim) (table built on the host).
+// ---------------------------------------------------------------------------------------------
+__global__ void rope_kv_kernel(const float *__restrict__ qkv, StepState s, const float *__restrict__ cs,
+                               void *q_out, void *kc, void *vc, int is_bf16, int H, int dh, int max_seq) {
+    const int r = blockIdx.x, hh = blockIdx.y, i = threadIdx.x;
+    const int half = dh >> 1, d = H * dh;
+    const int pos = s.row_pos[r], slot = s.row_slot[r];
+    const float c = cs[((size_t)pos * half + i) * 2], sn = cs[((size_t)pos * half + i) * 2 + 1];
+    const float *row = qkv + (size_t)r * 3 * d;
+    const float q1 = row[hh * dh + i], q2 = row[hh * dh + i + half];
+    const float k1 = row[d + hh * dh + i], k2 = row[d + hh * dh + i + half];
+    const float v1 = row[2 * d + hh * dh + i], v2 = row[2 * d + hh * dh + i + half];
+    const float qa = q1 * c - q2 * sn, qb = q2 * c + q1 * sn;
+    const float ka = k1 * c - k2 * sn, kb = k2 * c + k1 * sn;
+    const size_t head_base = ((size_t)slot * H + hh) * (size_t)max_seq * dh;
+    if (is_bf16) {
+        bf16_t *q = (bf16_t *)q_out + (size_t)r * d + hh * dh;
+        q[i] = f32_to_bf16(qa);
+        q[i + half] = f32_to_bf16(qb);
+        bf16_t *kp = (bf16_t *)kc + head_base, *vp = (bf16_t *)vc + head_base;
+        kp[kcache_off(pos, i, dh)] = f32_to_bf16(ka);
+        kp[kcache_off(pos, i + half, dh)] = f32_to_bf16(kb);
+        vp[vcache_off(pos, i, dh)] = f32_to_bf16(v1);
+        vp[vcache_off(pos, i + half, dh)] = f32_to_bf16(v2);
+    } else {
+        float *q = (float *)q_out + (size_t)r * d + hh * dh;
+        q[i] = qa;
+        q[i + half] = qb;
+        float *kp = (float *)kc + head_base + (size_t)pos * dh, *vp = (float *)vc + head_base + (size_t)pos * dh;
+        kp[i] = ka; kp[i + half] = kb;
+        vp[i] = v1; vp[i + half] = v2;
+    }
+}
+void launch_rope_kv(const float *qkv, const StepState &s, const float *cs_table, void *q_out, void *kc, void *vc,
+                    int is_bf16, int R, int H, int dh, int max_seq, hipStream_t st) {
+    hipLaunchKernelGGL(rope_kv_kernel, dim3(R, H), dim3(dh / 2), 0, st, qkv, s, cs_table, q_out, kc, vc, is_bf16, H, dh, max_seq);
+}
+
+// ---------------------------------------------------------------------------------------------
+// vocabulary arg max (lowest id on exact ties) + prefix accept + KV truncate
+// ---------------------------------------------------------------------------------------------
+// One workgroup per sequence.  o_j = arg max of row j for j = 0..keff; a = longest prefix with
+// o_i == draft_i; the step emits o_0..o_a, the cache keeps the rows of the pending token and
+// of the a accepted drafts (T += a + 1; rows beyond are overwritten by the next step), and
+// o_a becomes the pending token.
+__global__ __launch_bounds__(256) void argmax_accept_kernel(const float *__restrict__ pval, const int *__restrict__ pidx,
+                                                            int n_part, StepState s, int m, int max_k, const GenState *gen) {
+    __shared__ float wv[4];
+    __shared__ int wi[4];
+    __shared__ int o[40];
+    const int b = blockIdx.x;
+    const int keff = s.keff[b];
+    for (int j = 0; j <= keff; ++j) {
+        const size_t r = (size_t)b * m + j;
+        float bv = LLMA_NEG_INF;
+        int bi = 0x7fffffff;
+        for (int t = threadIdx.x; t < n_part; t += 256) {
+            float v = pval[r * n_part + t];
+            int id = pidx[r * n_part + t];
+            if (v > bv || (v == bv && id < bi)) { bv = v; bi = id; }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            float ov = __shfl_xor(bv, off);
+            int oi = __shfl_xor(bi, off);
+            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+        }
+        if ((threadIdx.x & 63) == 0) { wv[threadIdx.x >> 6] = bv; wi[threadIdx.x >> 6] = bi; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            for (int w = 1; w < 4; ++w)
+                if (wv[w] > bv || (wv[w] == bv && wi[w] < bi)) { bv = wv[w]; bi = wi[w]; }
+            o[j] = bi;
+            s.otok[r] = bi;
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x != 0) return;
+    int a = 0;
+    while (a < keff && o[a] == s.draft[b * max_k + a]) ++a;
+    const int slot = s.batch_slots[b];
+    s.nacc[b] = a;
+    s.next[b] = o[a];
+    for (int j = 0; j <= a; ++j) s.emit[b * (max_k + 1) + j] = o[j];
+    s.T[slot] += a + 1;
+    s.pending[slot] = o[a];
+    if (gen != nullptr && b == 0) {
+        int i = *gen->n_out, st = *gen->n_steps;
+        for (int j = 0; j <= a; ++j) gen->y[i + j] = o[j];
+        gen->trace[st * 4 + 0] = 1 + keff;
+        gen->trace[st * 4 + 1] = a + 1;
+        gen->trace[st * 4 + 2] = keff > 0 ? gen->cur[0] : -1;
+        gen->trace[st * 4 + 3] = keff > 0 ? gen->cur[1] : -1;
+        *gen->n_out = i + a + 1;
+        *gen->n_steps = st + 1;
+    }
+}
+void launch_argmax_accept(const float *pval, const int *pidx, int n_part, const StepState &s, int n_seqs, int m,
+                          int max_k, const GenState *gen, hipStream_t st) {
+    hipLaunchKernelGGL(argmax_accept_kernel, dim3(n_seqs), dim3(256), 0, st, pval, pidx, n_part, s, m, max_k, gen);
+}
+
+// ---------------------------------------------------------------------------------------------
+// trigger: wavefront-parallel scan of the reference for the n-token tail of y
+// ---------------------------------------------------------------------------------------------
+// Flat position p is a candidate when it lies at least n tokens into its document and the n
+// tokens before it equal the tail of y; its score is how far that agreement extends backwards
+// (bounded by the document start and by the start of y).  The best candidate maximises
+// (score, then smallest flat position) -- flat order is (document, position) order.
+__device__ __forceinline__ unsigned long long scan_reference(const int *y, int i, const int *ref, const int *doc_offsets,
+                                                             const int *ref_doc, int ref_len, int n) {
+    unsigned long long best = 0ull;
+    if (i >= n) {
+        for (int p = threadIdx.x; p < ref_len; p += blockDim.x) {
+            const int pos = p - doc_offsets[ref_doc[p]];
+            if (pos < n) continue;
+            bool ok = true;
+            for (int t = 0; t < n; ++t)
+                if (ref[p - 1 - t] != y[i - 1 - t]) { ok = false; break; }
+            if (!ok) continue;
+            int score = n;
+            while (score < pos && score < i && ref[p - 1 - score] == y[i - 1 - score]) ++score;
+            unsigned long long key = ((unsigned long long)score << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned)p);
+            best = key > best ? key : best;
+        }
+    }
+    // wave, then workgroup maximum
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        unsigned long long o = __shfl_xor(best, off);
+        best = o > best ? o : best;
+    }
+    __shared__ unsigned long long wbest[16];
+    if ((threadIdx.x & 63) == 0) wbest[threadIdx.x >> 6] = best;
+    __syncthreads();
+    const int waves = blockDim.x >> 6;
+    best = wbest[0];
+    for (int w = 1; w < waves; ++w) best = wbest[w] > best ? wbest[w] : best;
+    return best;
+}
+
+__global__ __launch_bounds__(256) void trigger_kernel(const GenState *gp, StepState s, int max_k) {
+    const GenState G = *gp;
+    const int i = *G.n_out;
+    unsigned long long best = 0ull;
+    if (G.ref_len > 0 && G.k > 0 && i < G.max_new)
+        best = scan_reference(G.y, i, G.ref, G.doc_offsets, G.ref_doc, G.ref_len, G.n);
+    int keff = 0, p = 0;
+    if (best != 0ull) {
+        p = (int)(0xFFFFFFFFu - (unsigned)(best & 0xFFFFFFFFull));
+        const int doc = G.ref_doc[p];
+        const int left_in_doc = G.doc_offsets[doc + 1] - p;
+        const int budget = G.max_new - i - 1;
+        keff = G.k < left_in_doc ? G.k : left_in_doc;
+        keff = keff < budget ? keff : budget;
+        keff = keff < 0 ? 0 : keff;
+        if (threadIdx.x == 0) { G.cur[0] = doc; G.cur[1] = p - G.doc_offsets[doc]; }
+    }
+    if (threadIdx.x == 0) s.keff[0] = keff;
+    for (int j = threadIdx.x; j < keff; j += blockDim.x) s.draft[j] = G.ref[p + j];
+}
+void launch_trigger(const GenState *gen_dev, const StepState &s, int max_k, hipStream_t st) {
+    hipLaunchKernelGGL(trigger_kernel, dim3(1), dim3(256), 0, st, gen_dev, s, max_k);
+}
+
+__global__ __launch_bounds__(256) void trigger_plain_kernel(const int *y, int y_len, const int *ref, const int *doc_offsets,
+                                                            const int *ref_doc, int ref_len, int n, int *result) {
+    unsigned long long best = scan_reference(y, y_len, ref, doc_offsets, ref_doc, ref_len, n);
+    if (threadIdx.x != 0) return;
+    if (best == 0ull) { result[0] = 0; result[1] = -1; result[2] = -1; return; }
+    int p = (int)(0xFFFFFFFFu - (unsigned)(best & 0xFFFFFFFFull));
+    int doc = ref_doc[p];
+    result[0] = 1; result[1] = doc; result[2] = p - doc_offsets[doc];
+}
+void launch_trigger_plain(const int *y, int y_len, const int *ref, const int *doc_offsets, const int *ref_doc,
+                          int ref_len, int n, int *result, hipStream_t st) {
+    hipLaunchKernelGGL(trigger_plain_kernel, dim3(1), dim3(256), 0, st, y, y_len, ref, doc_offsets, ref_doc, ref_len, n, result);
+}
+
+// ref_doc[p] = the document that contains flat position p (doc_offsets non-decreasing)
+__global__ void fill_ref_doc_kernel(const int *doc_offsets, int n_docs, int *ref_doc, int ref_len) {
+    int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= ref_len) return;
+    int lo = 0, hi = n_docs;              // largest j with doc_offsets[j] <= p
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (doc_offsets[mid] <= p) lo = mid; else hi = mid;
+    }
+    ref_doc[p] = lo;
+}
+void launch_fill_ref_doc(const int *doc_offsets, int n_docs, int *ref_doc, int ref_len, hipStream_t st) {
+    if (ref_len <= 0) return;
+    hipLaunchKernelGGL(fill_ref_doc_kernel, dim3((ref_len + 255) / 256), dim3(256), 0, st, doc_offsets, n_docs, ref_doc, ref_len);
+}

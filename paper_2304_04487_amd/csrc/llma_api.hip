@@ -1,0 +1,658 @@
+// C ABI of the library (include/llma.h) and the host orchestration of a decoding step:
+// which kernels run in which order for the verification forward (paper: Eq. 3), the accept /
+// truncate decision and the LLMA loop (paper: Algorithm 1).  All arithmetic of the method runs
+// in the kernels; this file validates arguments, owns device memory and enqueues launches.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/llma.h"
+#include "common.h"
+#include "kernels.h"
+
+static thread_local std::string g_err;      // errors of calls that have no context
+
+#define PREFILL_ROWS 32
+
+struct EventPair { hipEvent_t a, b; };
+
+struct llma_ctx {
+    llma_model_cfg cfg;
+    hipStream_t st = nullptr;
+    bool bf16 = false;
+    std::vector<void *> allocs;
+    int64_t dev_bytes = 0;
+    std::string err;
+
+    // weights (owned copies; bf16 matrices re-tiled)
+    void *embed = nullptr, *lm_head = nullptr;
+    float *final_norm = nullptr;
+    std::vector<void *> wqkv, wo, wgu, wd;
+    std::vector<float *> n1, n2;
+    // KV cache per layer: [max_batch][H][max_seq][dh]
+    std::vector<void *> kc, vc;
+    float *cs_table = nullptr;
+
+    // scratch for up to Rmax rows
+    int Rmax = 0;
+    float *h = nullptr, *qkv = nullptr;
+    void *xhi = nullptr, *xlo = nullptr, *q = nullptr, *att_hi = nullptr, *att_lo = nullptr, *act_hi = nullptr, *act_lo = nullptr;
+    float *po = nullptr, *pm = nullptr, *pl = nullptr;
+    int nc_max = 0;
+    float *pval = nullptr;
+    int *pidx = nullptr;
+    int n_part = 0;
+
+    StepState s{};
+    GenState gen{};               // host copy (device pointers inside)
+    GenState *gen_dev = nullptr;
+    int *gen_prompt = nullptr, *gen_ref = nullptr, *gen_doc_offsets = nullptr, *gen_ref_doc = nullptr;
+    int *gen_y = nullptr, *gen_trace = nullptr, *gen_counters = nullptr;   // counters: n_out, n_steps, cur[2]
+    int cap_prompt = 0, cap_ref = 0, cap_refdoc = 0, cap_docs = 0, cap_new = 0;
+
+    std::vector<int> T_host, pending_host, import_mask_layers;
+    float *logits_dump = nullptr;
+    int dump_rows = 0;
+    int opt_split = 1, opt_timing = 0, opt_graph = 1;
+    std::vector<EventPair> events;
+};
+
+static int fail(llma_ctx *c, int code, const char *fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (c) c->err = buf;
+    g_err = buf;
+    return code;
+}
+#define HIP_TRY(c, expr)                                                                             \
+    do {                                                                                             \
+        hipError_t e_ = (expr);                                                                      \
+        if (e_ != hipSuccess)                                                                        \
+            return fail((c), e_ == hipErrorOutOfMemory ? LLMA_E_NOMEM : LLMA_E_HIP, "%s: %s", #expr, \
+                        hipGetErrorString(e_));                                                      \
+    } while (0)
+
+static int dev_alloc(llma_ctx *c, void **p, size_t bytes) {
+    if (bytes == 0) bytes = 16;
+    hipError_t e = hipMalloc(p, bytes);
+    if (e != hipSuccess) return fail(c, LLMA_E_NOMEM, "hipMalloc(%zu bytes): %s", bytes, hipGetErrorString(e));
+    c->allocs.push_back(*p);
+    c->dev_bytes += (int64_t)bytes;
+    return LLMA_OK;
+}
+#define ALLOC(c, ptr, bytes)                                         \
+    do {                                                             \
+        int rc_ = dev_alloc((c), (void **)&(ptr), (size_t)(bytes));  \
+        if (rc_ != LLMA_OK) return rc_;                              \
+    } while (0)
+
+static void dev_free_one(llma_ctx *c, void *p) {
+    if (!p) return;
+    for (size_t i = 0; i < c->allocs.size(); ++i)
+        if (c->allocs[i] == p) { c->allocs.erase(c->allocs.begin() + i); break; }
+    (void)hipFree(p);
+}
+
+// ------------------------------------------------------------------------------------------------
+// create / destroy
+// ------------------------------------------------------------------------------------------------
+static int check_cfg(const llma_model_cfg *g) {
+    if (g->n_layers < 1 || g->d_model < 1 || g->n_heads < 1 || g->head_dim < 1 || g->d_ffn < 1 || g->vocab < 1)
+        return fail(nullptr, LLMA_E_INVAL, "model dimensions must be positive");
+    if (g->n_heads * g->head_dim != g->d_model) return fail(nullptr, LLMA_E_INVAL, "n_heads * head_dim != d_model");
+    if (g->max_seq < 2 || g->max_batch < 1 || g->max_k < 0 || g->max_k > 32)
+        return fail(nullptr, LLMA_E_INVAL, "need max_seq >= 2, max_batch >= 1, 0 <= max_k <= 32");
+    if (g->dtype == LLMA_DTYPE_BF16) {
+        if (g->d_model % 32 || g->d_ffn % 32 || g->vocab % 16)
+            return fail(nullptr, LLMA_E_INVAL, "bf16 needs d_model %% 32 == 0, d_ffn %% 32 == 0, vocab %% 16 == 0");
+        if (g->head_dim != 64 && g->head_dim != 128) return fail(nullptr, LLMA_E_INVAL, "bf16 needs head_dim 64 or 128");
+    } else if (g->dtype == LLMA_DTYPE_F32) {
+        if (g->head_dim != 32 && g->head_dim != 64 && g->head_dim != 128)
+            return fail(nullptr, LLMA_E_INVAL, "fp32 needs head_dim 32, 64 or 128");
+        if (g->d_model % 4) return fail(nullptr, LLMA_E_INVAL, "fp32 needs d_model %% 4 == 0");
+    } else {
+        return fail(nullptr, LLMA_E_INVAL, "unknown dtype %d", g->dtype);
+    }
+    if (!(g->rms_eps >= 0.f) || !(g->rope_theta > 0.f)) return fail(nullptr, LLMA_E_INVAL, "bad rms_eps / rope_theta");
+    return LLMA_OK;
+}
+
+static int take_matrix(llma_ctx *c, void **dst, const void *src, int N, int K) {
+    size_t bytes = (size_t)N * K * (c->bf16 ? 2 : 4);
+    ALLOC(c, *dst, bytes);
+    if (c->bf16) launch_pack_weight(src, *dst, N, K, c->st);
+    else HIP_TRY(c, hipMemcpyAsync(*dst, src, bytes, hipMemcpyDeviceToDevice, c->st));
+    return LLMA_OK;
+}
+
+static int create_impl(llma_ctx *c, const llma_weights *w) {
+    const llma_model_cfg &g = c->cfg;
+    const int L = g.n_layers, d = g.d_model, F = g.d_ffn, V = g.vocab, H = g.n_heads, dh = g.head_dim;
+    const size_t es = c->bf16 ? 2 : 4;
+    // ---- weights
+    ALLOC(c, c->embed, (size_t)V * d * es);
+    HIP_TRY(c, hipMemcpyAsync(c->embed, w->embed, (size_t)V * d * es, hipMemcpyDeviceToDevice, c->st));
+    int rc = take_matrix(c, &c->lm_head, w->lm_head, V, d);
+    if (rc) return rc;
+    ALLOC(c, c->final_norm, d * 4);
+    HIP_TRY(c, hipMemcpyAsync(c->final_norm, w->final_norm, d * 4, hipMemcpyDeviceToDevice, c->st));
+    c->wqkv.assign(L, nullptr); c->wo.assign(L, nullptr); c->wgu.assign(L, nullptr); c->wd.assign(L, nullptr);
+    c->n1.assign(L, nullptr); c->n2.assign(L, nullptr); c->kc.assign(L, nullptr); c->vc.assign(L, nullptr);
+    for (int l = 0; l < L; ++l) {
+        if (!w->wqkv[l] || !w->wo[l] || !w->wgu[l] || !w->wdown[l] || !w->norm1[l] || !w->norm2[l])
+            return fail(c, LLMA_E_INVAL, "null weight pointer in layer %d", l);
+        if ((rc = take_matrix(c, &c->wqkv[l], w->wqkv[l], 3 * d, d))) return rc;
+        if ((rc = take_matrix(c, &c->wo[l], w->wo[l], d, d))) return rc;
+        if ((rc = take_matrix(c, &c->wgu[l], w->wgu[l], 2 * F, d))) return rc;
+        if ((rc = take_matrix(c, &c->wd[l], w->wdown[l], d, F))) return rc;
+        ALLOC(c, c->n1[l], d * 4);
+        ALLOC(c, c->n2[l], d * 4);
+        HIP_TRY(c, hipMemcpyAsync(c->n1[l], w->norm1[l], d * 4, hipMemcpyDeviceToDevice, c->st));
+        HIP_TRY(c, hipMemcpyAsync(c->n2[l], w->norm2[l], d * 4, hipMemcpyDeviceToDevice, c->st));
+    }
+    // ---- KV cache, zero-filled so that never-written positions hold finite values
+    const size_t kv_bytes = (size_t)g.max_batch * H * g.max_seq * dh * es;
+    for (int l = 0; l < L; ++l) {
+        ALLOC(c, c->kc[l], kv_bytes);
+        ALLOC(c, c->vc[l], kv_bytes);
+        HIP_TRY(c, hipMemsetAsync(c->kc[l], 0, kv_bytes, c->st));
+        HIP_TRY(c, hipMemsetAsync(c->vc[l], 0, kv_bytes, c->st));
+    }
+    // ---- rotary table: cos/sin(pos * theta^(-2i/dh)) in double, stored fp32
+    {
+        const int half = dh / 2;
+        std::vector<float> cs((size_t)g.max_seq * half * 2);
+        for (int i = 0; i < half; ++i) {
+            const double inv = pow((double)g.rope_theta, -2.0 * i / (double)dh);
+            for (int p = 0; p < g.max_seq; ++p) {
+                const double ang = (double)p * inv;
+                cs[((size_t)p * half + i) * 2] = (float)cos(ang);
+                cs[((size_t)p * half + i) * 2 + 1] = (float)sin(ang);
+            }
+        }
+        ALLOC(c, c->cs_table, cs.size() * 4);
+        HIP_TRY(c, hipMemcpy(c->cs_table, cs.data(), cs.size() * 4, hipMemcpyHostToDevice));
+    }
+    // ---- scratch
+    const int m_max = g.max_k + 1;
+    c->Rmax = g.max_batch * m_max;
+    if (c->Rmax < PREFILL_ROWS) c->Rmax = PREFILL_ROWS;
+    const size_t Rp = (size_t)c->Rmax + 48;                  // slack: the GEMM reads whole 16-row tiles
+    ALLOC(c, c->h, Rp * d * 4);
+    ALLOC(c, c->qkv, Rp * 3 * d * 4);
+    ALLOC(c, c->xhi, Rp * d * es);
+    ALLOC(c, c->xlo, Rp * d * es);
+    ALLOC(c, c->q, Rp * d * es);
+    ALLOC(c, c->att_hi, Rp * d * es);
+    ALLOC(c, c->att_lo, Rp * d * es);
+    ALLOC(c, c->act_hi, Rp * F * es);
+    ALLOC(c, c->act_lo, Rp * F * es);
+    void *zero_these[] = {c->h, c->qkv, c->xhi, c->xlo, c->q, c->att_hi, c->att_lo, c->act_hi, c->act_lo};
+    size_t zero_bytes[] = {Rp * d * 4, Rp * 3 * d * 4, Rp * d * es, Rp * d * es, Rp * d * es, Rp * d * es, Rp * d * es, Rp * F * es, Rp * F * es};
+    for (int i = 0; i < 9; ++i) HIP_TRY(c, hipMemsetAsync(zero_these[i], 0, zero_bytes[i], c->st));
+    if (c->bf16) {
+        c->nc_max = (g.max_seq + ATTN_CHUNK - 1) / ATTN_CHUNK;
+        const size_t np = (size_t)g.max_batch * H * c->nc_max * 48;
+        ALLOC(c, c->po, np * dh * 4);
+        ALLOC(c, c->pm, np * 4);
+        ALLOC(c, c->pl, np * 4);
+    }
+    c->n_part = c->bf16 ? V / 16 : V;
+    ALLOC(c, c->pval, (size_t)c->Rmax * c->n_part * 4);
+    ALLOC(c, c->pidx, (size_t)c->Rmax * c->n_part * 4);
+    // ---- step state
+    StepState &s = c->s;
+    ALLOC(c, s.row_tok, Rp * 4);
+    ALLOC(c, s.row_pos, Rp * 4);
+    ALLOC(c, s.row_slot, Rp * 4);
+    ALLOC(c, s.T, g.max_batch * 4);
+    ALLOC(c, s.pending, g.max_batch * 4);
+    ALLOC(c, s.batch_slots, g.max_batch * 4);
+    ALLOC(c, s.keff, g.max_batch * 4);
+    ALLOC(c, s.draft, (size_t)g.max_batch * (g.max_k + 1) * 4);
+    ALLOC(c, s.nacc, g.max_batch * 4);
+    ALLOC(c, s.next, g.max_batch * 4);
+    ALLOC(c, s.emit, (size_t)g.max_batch * m_max * 4);
+    ALLOC(c, s.otok, Rp * 4);
+    HIP_TRY(c, hipMemsetAsync(s.T, 0, g.max_batch * 4, c->st));
+    HIP_TRY(c, hipMemsetAsync(s.pending, 0xFF, g.max_batch * 4, c->st));
+    HIP_TRY(c, hipMemsetAsync(s.keff, 0, g.max_batch * 4, c->st));
+    ALLOC(c, c->gen_dev, sizeof(GenState));
+    ALLOC(c, c->gen_counters, 4 * 4);
+    c->T_host.assign(g.max_batch, 0);
+    c->pending_host.assign(g.max_batch, -1);
+    c->import_mask_layers.assign(g.max_batch, 0);
+    HIP_TRY(c, hipStreamSynchronize(c->st));
+    HIP_TRY(c, hipGetLastError());
+    return LLMA_OK;
+}
+
+extern "C" int llma_create(const llma_model_cfg *cfg, const llma_weights *w, void *hip_stream, llma_ctx **out) {
+    if (!cfg || !w || !out) return fail(nullptr, LLMA_E_INVAL, "llma_create: null argument");
+    *out = nullptr;
+    int rc = check_cfg(cfg);
+    if (rc) return rc;
+    if (!w->embed || !w->lm_head || !w->final_norm || !w->wqkv || !w->wo || !w->wgu || !w->wdown || !w->norm1 || !w->norm2)
+        return fail(nullptr, LLMA_E_INVAL, "llma_create: null weight pointer");
+    llma_ctx *c = new (std::nothrow) llma_ctx();
+    if (!c) return fail(nullptr, LLMA_E_NOMEM, "llma_create: host allocation failed");
+    c->cfg = *cfg;
+    c->st = (hipStream_t)hip_stream;
+    c->bf16 = cfg->dtype == LLMA_DTYPE_BF16;
+    rc = create_impl(c, w);
+    if (rc) {
+        std::string e = c->err;
+        llma_destroy(c);
+        g_err = e;
+        return rc;
+    }
+    *out = c;
+    return LLMA_OK;
+}
+
+extern "C" int llma_destroy(llma_ctx *c) {
+    if (!c) return LLMA_OK;
+    (void)hipStreamSynchronize(c->st);
+    for (auto &e : c->events) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
+    for (void *p : c->allocs) (void)hipFree(p);
+    delete c;
+    return LLMA_OK;
+}
+
+extern "C" const char *llma_last_error(const llma_ctx *c) { return c ? c->err.c_str() : g_err.c_str(); }
+extern "C" int64_t llma_device_bytes(const llma_ctx *c) { return c ? c->dev_bytes : 0; }
+
+// ------------------------------------------------------------------------------------------------
+// the forward over the rows described by ctx->s.row_* (paper: Eq. 3)
+// ------------------------------------------------------------------------------------------------
+static int forward(llma_ctx *c, int n_seqs, int m, int t_max, bool lm_head) {
+    const llma_model_cfg &g = c->cfg;
+    const int d = g.d_model, F = g.d_ffn, V = g.vocab, H = g.n_heads, dh = g.head_dim, L = g.n_layers;
+    const int R = n_seqs * m;
+    const int isb = c->bf16 ? 1 : 0;
+    hipStream_t st = c->st;
+    launch_embed(c->embed, isb, c->s.row_tok, c->h, R, d, st);
+    GemmArgs ga{};
+    ga.split = c->bf16 && c->opt_split;
+    ga.rows = R;
+    AttnArgs aa{};
+    aa.Q = c->q; aa.T = c->s.T; aa.batch_slots = c->s.batch_slots; aa.n_seqs = n_seqs; aa.m = m; aa.H = H; aa.dh = dh;
+    aa.max_seq = g.max_seq; aa.n_chunks = (t_max + m + ATTN_CHUNK - 1) / ATTN_CHUNK; aa.scale = 1.0f / sqrtf((float)dh);
+    aa.po = c->po; aa.pm = c->pm; aa.pl = c->pl; aa.out_hi = c->att_hi; aa.out_lo = c->att_lo;
+    for (int l = 0; l < L; ++l) {
+        launch_rmsnorm(c->h, c->n1[l], g.rms_eps, c->xhi, c->xlo, isb, R, d, st);
+        ga.W = c->wqkv[l]; ga.Xhi = c->xhi; ga.Xlo = c->xlo; ga.N = 3 * d; ga.K = d; ga.epi = EPI_STORE; ga.out = c->qkv;
+        isb ? launch_gemm_bf16(ga, st) : launch_gemm_f32(ga, st);
+        launch_rope_kv(c->qkv, c->s, c->cs_table, c->q, c->kc[l], c->vc[l], isb, R, H, dh, g.max_seq, st);
+        aa.Kc = c->kc[l]; aa.Vc = c->vc[l];
+        isb ? launch_attn_bf16(aa, st) : launch_attn_f32(aa, st);
+        ga.W = c->wo[l]; ga.Xhi = c->att_hi; ga.Xlo = c->att_lo; ga.N = d; ga.K = d; ga.epi = EPI_RESID; ga.out = c->h;
+        isb ? launch_gemm_bf16(ga, st) : launch_gemm_f32(ga, st);
+        launch_rmsnorm(c->h, c->n2[l], g.rms_eps, c->xhi, c->xlo, isb, R, d, st);
+        ga.W = c->wgu[l]; ga.Xhi = c->xhi; ga.Xlo = c->xlo; ga.N = F; ga.K = d; ga.epi = EPI_SWIGLU; ga.out = nullptr;
+        ga.act_hi = c->act_hi; ga.act_lo = c->act_lo;
+        if (c->opt_timing) {
+            EventPair ep;
+            HIP_TRY(c, hipEventCreate(&ep.a));
+            HIP_TRY(c, hipEventCreate(&ep.b));
+            HIP_TRY(c, hipEventRecord(ep.a, st));
+            isb ? launch_gemm_bf16(ga, st) : launch_gemm_f32(ga, st);
+            HIP_TRY(c, hipEventRecord(ep.b, st));
+            c->events.push_back(ep);
+        } else {
+            isb ? launch_gemm_bf16(ga, st) : launch_gemm_f32(ga, st);
+        }
+        ga.W = c->wd[l]; ga.Xhi = c->act_hi; ga.Xlo = c->act_lo; ga.N = d; ga.K = F; ga.epi = EPI_RESID; ga.out = c->h;
+        ga.act_hi = ga.act_lo = nullptr;
+        isb ? launch_gemm_bf16(ga, st) : launch_gemm_f32(ga, st);
+    }
+    if (lm_head) {
+        launch_rmsnorm(c->h, c->final_norm, g.rms_eps, c->xhi, c->xlo, isb, R, d, st);
+        ga.W = c->lm_head; ga.Xhi = c->xhi; ga.Xlo = c->xlo; ga.N = V; ga.K = d; ga.epi = EPI_LMHEAD;
+        ga.out = c->logits_dump; ga.pval = c->pval; ga.pidx = c->pidx; ga.n_part = c->n_part;
+        isb ? launch_gemm_bf16(ga, st) : launch_gemm_f32(ga, st);
+    }
+    HIP_TRY(c, hipGetLastError());
+    return LLMA_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// sequence state
+// ------------------------------------------------------------------------------------------------
+static int check_slot(llma_ctx *c, int seq, const char *who) {
+    if (!c) return fail(nullptr, LLMA_E_INVAL, "%s: null context", who);
+    if (seq < 0 || seq >= c->cfg.max_batch) return fail(c, LLMA_E_RANGE, "%s: slot %d outside [0,%d)", who, seq, c->cfg.max_batch);
+    return LLMA_OK;
+}
+static int push_state(llma_ctx *c, int seq) {       // host mirror -> device
+    HIP_TRY(c, hipMemcpyAsync(c->s.T + seq, &c->T_host[seq], 4, hipMemcpyHostToDevice, c->st));
+    HIP_TRY(c, hipMemcpyAsync(c->s.pending + seq, &c->pending_host[seq], 4, hipMemcpyHostToDevice, c->st));
+    HIP_TRY(c, hipStreamSynchronize(c->st));
+    return LLMA_OK;
+}
+
+extern "C" int llma_reset(llma_ctx *c, int32_t seq) {
+    int rc = check_slot(c, seq, "llma_reset");
+    if (rc) return rc;
+    c->T_host[seq] = 0;
+    c->pending_host[seq] = -1;
+    c->import_mask_layers[seq] = 0;
+    return push_state(c, seq);
+}
+
+extern "C" int llma_get_state(llma_ctx *c, int32_t seq, int32_t *T, int32_t *pending) {
+    int rc = check_slot(c, seq, "llma_get_state");
+    if (rc) return rc;
+    int t = 0, p = -1;
+    HIP_TRY(c, hipMemcpyAsync(&t, c->s.T + seq, 4, hipMemcpyDeviceToHost, c->st));
+    HIP_TRY(c, hipMemcpyAsync(&p, c->s.pending + seq, 4, hipMemcpyDeviceToHost, c->st));
+    HIP_TRY(c, hipStreamSynchronize(c->st));
+    if (T) *T = t;
+    if (pending) *pending = p;
+    return LLMA_OK;
+}
+
+extern "C" int llma_set_pending(llma_ctx *c, int32_t seq, int32_t token) {
+    int rc = check_slot(c, seq, "llma_set_pending");
+    if (rc) return rc;
+    if (token < 0 || token >= c->cfg.vocab) return fail(c, LLMA_E_RANGE, "llma_set_pending: token %d outside [0,%d)", token, c->cfg.vocab);
+    c->pending_host[seq] = token;
+    return push_state(c, seq);
+}
+
+extern "C" int llma_kv_import(llma_ctx *c, int32_t seq, int32_t layer, const void *k, const void *v, int32_t len) {
+    int rc = check_slot(c, seq, "llma_kv_import");
+    if (rc) return rc;
+    if (!k || !v) return fail(c, LLMA_E_INVAL, "llma_kv_import: null pointer");
+    if (layer < 0 || layer >= c->cfg.n_layers) return fail(c, LLMA_E_RANGE, "llma_kv_import: layer %d", layer);
+    if (len < 0 || len > c->cfg.max_seq) return fail(c, LLMA_E_RANGE, "llma_kv_import: len %d > max_seq %d", len, c->cfg.max_seq);
+    const llma_model_cfg &g = c->cfg;
+    const size_t es = c->bf16 ? 2 : 4;
+    const size_t slot_off = (size_t)seq * g.n_heads * g.max_seq * g.head_dim * es;
+    void *kc = (char *)c->kc[layer] + slot_off, *vc = (char *)c->vc[layer] + slot_off;
+    if (len > 0) {
+        if (c->bf16) launch_kv_import_bf16(k, v, kc, vc, g.n_heads, len, g.head_dim, g.max_seq, c->st);
+        else launch_kv_import_f32(k, v, kc, vc, g.n_heads, len, g.head_dim, g.max_seq, c->st);
+    }
+    HIP_TRY(c, hipGetLastError());
+    if (layer == g.n_layers - 1) {
+        c->T_host[seq] = len;
+        return push_state(c, seq);
+    }
+    return LLMA_OK;
+}
+
+static int check_tokens(llma_ctx *c, const int32_t *t, int n, const char *who) {
+    for (int i = 0; i < n; ++i)
+        if (t[i] < 0 || t[i] >= c->cfg.vocab) return fail(c, LLMA_E_RANGE, "%s: token[%d] = %d outside [0,%d)", who, i, t[i], c->cfg.vocab);
+    return LLMA_OK;
+}
+
+// feeds prompt_dev[0..len-1) in chunks; rows only write KV, no LM head
+static int prefill_rows(llma_ctx *c, int seq, const int *prompt_dev, int n_feed) {
+    for (int off = 0; off < n_feed; off += PREFILL_ROWS) {
+        const int m = n_feed - off < PREFILL_ROWS ? n_feed - off : PREFILL_ROWS;
+        launch_setup_prefill_rows(c->s, prompt_dev, off, m, seq, c->st);
+        int rc = forward(c, 1, m, c->T_host[seq], false);
+        if (rc) return rc;
+        launch_advance_T(c->s, seq, m, c->st);
+        c->T_host[seq] += m;
+    }
+    return LLMA_OK;
+}
+
+static int ensure_cap(llma_ctx *c, int **buf, int *cap, int need) {
+    if (need <= *cap) return LLMA_OK;
+    HIP_TRY(c, hipStreamSynchronize(c->st));
+    if (*buf) { dev_free_one(c, *buf); *buf = nullptr; *cap = 0; }
+    int ncap = need + need / 2 + 64;
+    ALLOC(c, *buf, (size_t)ncap * 4);
+    *cap = ncap;
+    return LLMA_OK;
+}
+
+extern "C" int llma_prefill(llma_ctx *c, int32_t seq, const int32_t *prompt, int32_t len) {
+    int rc = check_slot(c, seq, "llma_prefill");
+    if (rc) return rc;
+    if (!prompt || len < 1) return fail(c, LLMA_E_INVAL, "llma_prefill: need a prompt of at least one token");
+    if (c->T_host[seq] + len > c->cfg.max_seq)
+        return fail(c, LLMA_E_RANGE, "llma_prefill: T %d + len %d > max_seq %d", c->T_host[seq], len, c->cfg.max_seq);
+    if ((rc = check_tokens(c, prompt, len, "llma_prefill"))) return rc;
+    if ((rc = ensure_cap(c, &c->gen_prompt, &c->cap_prompt, len))) return rc;
+    HIP_TRY(c, hipMemcpyAsync(c->gen_prompt, prompt, (size_t)len * 4, hipMemcpyHostToDevice, c->st));
+    if ((rc = prefill_rows(c, seq, c->gen_prompt, len - 1))) return rc;
+    c->pending_host[seq] = prompt[len - 1];
+    HIP_TRY(c, hipMemcpyAsync(c->s.pending + seq, &c->pending_host[seq], 4, hipMemcpyHostToDevice, c->st));
+    HIP_TRY(c, hipStreamSynchronize(c->st));
+    return LLMA_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// llma_find_trigger (stateless)
+// ------------------------------------------------------------------------------------------------
+extern "C" int llma_find_trigger(const int32_t *y, int32_t y_len, const int32_t *ref, const int32_t *doc_offsets,
+                                 int32_t n_docs, int32_t n, int32_t *doc_out, int32_t *pos_out) {
+    if (!doc_out || !pos_out || !doc_offsets || n_docs < 0 || y_len < 0 || (!y && y_len > 0))
+        return fail(nullptr, LLMA_E_INVAL, "llma_find_trigger: null pointer or negative count");
+    if (n < 1) return fail(nullptr, LLMA_E_INVAL, "llma_find_trigger: n must be >= 1");
+    for (int j = 0; j < n_docs; ++j)
+        if (doc_offsets[j + 1] < doc_offsets[j] || doc_offsets[0] != 0)
+            return fail(nullptr, LLMA_E_INVAL, "llma_find_trigger: doc_offsets must start at 0 and be non-decreasing");
+    *doc_out = -1;
+    *pos_out = -1;
+    const int ref_len = n_docs > 0 ? doc_offsets[n_docs] : 0;
+    if (ref_len > 0 && !ref) return fail(nullptr, LLMA_E_INVAL, "llma_find_trigger: null reference");
+    if (ref_len == 0 || y_len < n) return 0;
+    int *buf = nullptr;
+    const size_t ints = (size_t)y_len + 2 * (size_t)ref_len + (n_docs + 1) + 4;
+    hipError_t e = hipMalloc((void **)&buf, ints * 4);
+    if (e != hipSuccess) return fail(nullptr, LLMA_E_NOMEM, "llma_find_trigger: hipMalloc: %s", hipGetErrorString(e));
+    int *dy = buf, *dref = dy + y_len, *ddoc = dref + ref_len, *doff = ddoc + ref_len, *dres = doff + n_docs + 1;
+    int res[3] = {0, -1, -1};
+    e = hipMemcpy(dy, y, (size_t)y_len * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(dref, ref, (size_t)ref_len * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(doff, doc_offsets, (size_t)(n_docs + 1) * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) {
+        launch_fill_ref_doc(doff, n_docs, ddoc, ref_len, nullptr);
+        launch_trigger_plain(dy, y_len, dref, doff, ddoc, ref_len, n, dres, nullptr);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipMemcpy(res, dres, 12, hipMemcpyDeviceToHost);
+    (void)hipFree(buf);
+    if (e != hipSuccess) return fail(nullptr, LLMA_E_HIP, "llma_find_trigger: %s", hipGetErrorString(e));
+    if (res[0]) { *doc_out = res[1]; *pos_out = res[2]; }
+    return res[0];
+}
+
+// ------------------------------------------------------------------------------------------------
+// verify step
+// ------------------------------------------------------------------------------------------------
+extern "C" int llma_verify_step_batch(llma_ctx *c, int32_t n_seqs, const int32_t *seqs, const int32_t *drafts, int32_t k,
+                                      int32_t *n_accepted, int32_t *next_token, int32_t *emitted) {
+    if (!c) return fail(nullptr, LLMA_E_INVAL, "llma_verify_step: null context");
+    const llma_model_cfg &g = c->cfg;
+    if (!seqs || n_seqs < 1 || n_seqs > g.max_batch) return fail(c, LLMA_E_INVAL, "llma_verify_step: bad slot list");
+    if (k < 0 || k > g.max_k) return fail(c, LLMA_E_RANGE, "llma_verify_step: k %d outside [0, max_k %d]", k, g.max_k);
+    if (k > 0 && !drafts) return fail(c, LLMA_E_INVAL, "llma_verify_step: null drafts with k > 0");
+    int t_max = 0;
+    for (int b = 0; b < n_seqs; ++b) {
+        int rc = check_slot(c, seqs[b], "llma_verify_step");
+        if (rc) return rc;
+        for (int b2 = 0; b2 < b; ++b2)
+            if (seqs[b2] == seqs[b]) return fail(c, LLMA_E_INVAL, "llma_verify_step: slot %d listed twice", seqs[b]);
+        if (c->pending_host[seqs[b]] < 0) return fail(c, LLMA_E_STATE, "llma_verify_step: slot %d has no pending token", seqs[b]);
+        if (c->T_host[seqs[b]] + k + 1 > g.max_seq)
+            return fail(c, LLMA_E_RANGE, "llma_verify_step: T %d + k + 1 > max_seq %d", c->T_host[seqs[b]], g.max_seq);
+        if (c->T_host[seqs[b]] > t_max) t_max = c->T_host[seqs[b]];
+    }
+    if (k > 0) {
+        int rc = check_tokens(c, drafts, n_seqs * k, "llma_verify_step(draft)");
+        if (rc) return rc;
+    }
+    if (c->logits_dump && n_seqs * (k + 1) > c->dump_rows)
+        return fail(c, LLMA_E_RANGE, "llma_verify_step: logits dump holds %d rows, step has %d", c->dump_rows, n_seqs * (k + 1));
+    const int m = k + 1, mk = g.max_k;
+    hipStream_t st = c->st;
+    std::vector<int> keff(n_seqs, k), dr((size_t)n_seqs * (mk > 0 ? mk : 1), 0);
+    for (int b = 0; b < n_seqs; ++b)
+        for (int j = 0; j < k; ++j) dr[(size_t)b * mk + j] = drafts[(size_t)b * k + j];
+    HIP_TRY(c, hipMemcpyAsync(c->s.batch_slots, seqs, (size_t)n_seqs * 4, hipMemcpyHostToDevice, st));
+    HIP_TRY(c, hipMemcpyAsync(c->s.keff, keff.data(), (size_t)n_seqs * 4, hipMemcpyHostToDevice, st));
+    if (k > 0) HIP_TRY(c, hipMemcpyAsync(c->s.draft, dr.data(), (size_t)n_seqs * mk * 4, hipMemcpyHostToDevice, st));
+    launch_setup_step_rows(c->s, n_seqs, m, mk, st);
+    int rc = forward(c, n_seqs, m, t_max, true);
+    if (rc) return rc;
+    launch_argmax_accept(c->pval, c->pidx, c->n_part, c->s, n_seqs, m, mk, nullptr, st);
+    std::vector<int> nacc(n_seqs), nxt(n_seqs), em((size_t)n_seqs * (mk + 1));
+    HIP_TRY(c, hipMemcpyAsync(nacc.data(), c->s.nacc, (size_t)n_seqs * 4, hipMemcpyDeviceToHost, st));
+    HIP_TRY(c, hipMemcpyAsync(nxt.data(), c->s.next, (size_t)n_seqs * 4, hipMemcpyDeviceToHost, st));
+    HIP_TRY(c, hipMemcpyAsync(em.data(), c->s.emit, (size_t)n_seqs * (mk + 1) * 4, hipMemcpyDeviceToHost, st));
+    HIP_TRY(c, hipStreamSynchronize(st));
+    HIP_TRY(c, hipGetLastError());
+    for (int b = 0; b < n_seqs; ++b) {
+        c->T_host[seqs[b]] += nacc[b] + 1;
+        c->pending_host[seqs[b]] = nxt[b];
+        if (n_accepted) n_accepted[b] = nacc[b];
+        if (next_token) next_token[b] = nxt[b];
+        if (emitted)
+            for (int j = 0; j <= nacc[b]; ++j) emitted[(size_t)b * (k + 1) + j] = em[(size_t)b * (mk + 1) + j];
+    }
+    return LLMA_OK;
+}
+
+extern "C" int llma_verify_step(llma_ctx *c, int32_t seq, const int32_t *draft, int32_t k, int32_t *n_accepted,
+                                int32_t *next_token, int32_t *emitted) {
+    return llma_verify_step_batch(c, 1, &seq, draft, k, n_accepted, next_token, emitted);
+}
+
+// ------------------------------------------------------------------------------------------------
+// llma_generate (paper: Algorithm 1)
+// ------------------------------------------------------------------------------------------------
+extern "C" int llma_generate(llma_ctx *c, int32_t seq, const int32_t *prompt, int32_t prompt_len, const int32_t *ref,
+                             const int32_t *doc_offsets, int32_t n_docs, int32_t n, int32_t k, int32_t max_new,
+                             int32_t *out_tokens, int32_t *n_out, llma_step_rec *trace, int32_t *n_steps) {
+    int rc = check_slot(c, seq, "llma_generate");
+    if (rc) return rc;
+    const llma_model_cfg &g = c->cfg;
+    if (!prompt || prompt_len < 1 || !out_tokens || !n_out || max_new < 1) return fail(c, LLMA_E_INVAL, "llma_generate: null / empty argument");
+    if (n < 1) return fail(c, LLMA_E_INVAL, "llma_generate: n must be >= 1");
+    if (k < 0 || k > g.max_k) return fail(c, LLMA_E_RANGE, "llma_generate: k %d outside [0, max_k %d]", k, g.max_k);
+    if (n_docs < 0 || (n_docs > 0 && !doc_offsets)) return fail(c, LLMA_E_INVAL, "llma_generate: bad documents");
+    int ref_len = 0;
+    if (n_docs > 0) {
+        if (doc_offsets[0] != 0) return fail(c, LLMA_E_INVAL, "llma_generate: doc_offsets[0] != 0");
+        for (int j = 0; j < n_docs; ++j)
+            if (doc_offsets[j + 1] < doc_offsets[j]) return fail(c, LLMA_E_INVAL, "llma_generate: doc_offsets decrease at %d", j);
+        ref_len = doc_offsets[n_docs];
+        if (ref_len > 0 && !ref) return fail(c, LLMA_E_INVAL, "llma_generate: null reference");
+    }
+    if ((long)prompt_len + max_new + k > g.max_seq)
+        return fail(c, LLMA_E_RANGE, "llma_generate: prompt %d + max_new %d + k %d > max_seq %d", prompt_len, max_new, k, g.max_seq);
+    if ((rc = check_tokens(c, prompt, prompt_len, "llma_generate(prompt)"))) return rc;
+    if (ref_len && (rc = check_tokens(c, ref, ref_len, "llma_generate(ref)"))) return rc;
+    if (c->logits_dump && k + 1 > c->dump_rows) return fail(c, LLMA_E_RANGE, "llma_generate: logits dump too small");
+
+    hipStream_t st = c->st;
+    if ((rc = ensure_cap(c, &c->gen_prompt, &c->cap_prompt, prompt_len))) return rc;
+    if ((rc = ensure_cap(c, &c->gen_ref, &c->cap_ref, ref_len))) return rc;
+    if ((rc = ensure_cap(c, &c->gen_ref_doc, &c->cap_refdoc, ref_len))) return rc;
+    if ((rc = ensure_cap(c, &c->gen_doc_offsets, &c->cap_docs, n_docs + 1))) return rc;
+    if (max_new > c->cap_new) {
+        int cy = 0, ct = 0;
+        if (c->gen_y) { HIP_TRY(c, hipStreamSynchronize(st)); dev_free_one(c, c->gen_y); dev_free_one(c, c->gen_trace); c->gen_y = c->gen_trace = nullptr; }
+        if ((rc = ensure_cap(c, &c->gen_y, &cy, max_new + 64))) return rc;
+        if ((rc = ensure_cap(c, &c->gen_trace, &ct, 4 * (max_new + 64)))) return rc;
+        c->cap_new = max_new;
+    }
+    HIP_TRY(c, hipMemcpyAsync(c->gen_prompt, prompt, (size_t)prompt_len * 4, hipMemcpyHostToDevice, st));
+    if (ref_len) HIP_TRY(c, hipMemcpyAsync(c->gen_ref, ref, (size_t)ref_len * 4, hipMemcpyHostToDevice, st));
+    int zero_off = 0;
+    HIP_TRY(c, hipMemcpyAsync(c->gen_doc_offsets, n_docs > 0 ? doc_offsets : &zero_off, (size_t)(n_docs + 1) * 4, hipMemcpyHostToDevice, st));
+    launch_fill_ref_doc(c->gen_doc_offsets, n_docs, c->gen_ref_doc, ref_len, st);
+    HIP_TRY(c, hipMemsetAsync(c->gen_counters, 0, 16, st));
+    GenState &G = c->gen;
+    G.y = c->gen_y; G.n_out = c->gen_counters; G.n_steps = c->gen_counters + 1; G.cur = c->gen_counters + 2; G.trace = c->gen_trace;
+    G.ref = c->gen_ref; G.doc_offsets = c->gen_doc_offsets; G.ref_doc = c->gen_ref_doc; G.ref_len = ref_len; G.n_docs = n_docs;
+    G.n = n; G.k = k; G.max_new = max_new; G.prompt = c->gen_prompt;
+    HIP_TRY(c, hipMemcpyAsync(c->gen_dev, &G, sizeof(GenState), hipMemcpyHostToDevice, st));
+    HIP_TRY(c, hipStreamSynchronize(st));     // G and the host staging buffers may go out of scope / change
+
+    // ---- x: reset the slot, feed prompt[0..len-2], prompt[len-1] becomes the pending token
+    c->T_host[seq] = 0;
+    c->pending_host[seq] = prompt[prompt_len - 1];
+    c->import_mask_layers[seq] = 0;
+    if ((rc = push_state(c, seq))) return rc;
+    if ((rc = prefill_rows(c, seq, c->gen_prompt, prompt_len - 1))) return rc;
+
+    // ---- the decoding loop: trigger -> rows -> forward -> accept, all on the device; the host
+    //      only reads the output count back to know when to stop
+    const int m = k + 1, mk = g.max_k;
+    HIP_TRY(c, hipMemcpyAsync(c->s.batch_slots, &seq, 4, hipMemcpyHostToDevice, st));
+    int produced = 0, steps = 0;
+    while (produced < max_new) {
+        launch_trigger(c->gen_dev, c->s, mk, st);
+        launch_setup_step_rows(c->s, 1, m, mk, st);
+        if ((rc = forward(c, 1, m, c->T_host[seq], true))) return rc;
+        launch_argmax_accept(c->pval, c->pidx, c->n_part, c->s, 1, m, mk, c->gen_dev, st);
+        int now = 0;
+        HIP_TRY(c, hipMemcpyAsync(&now, G.n_out, 4, hipMemcpyDeviceToHost, st));
+        HIP_TRY(c, hipStreamSynchronize(st));
+        if (now <= produced || now > max_new) return fail(c, LLMA_E_HIP, "llma_generate: device output count went %d -> %d", produced, now);
+        c->T_host[seq] += now - produced;
+        produced = now;
+        ++steps;
+    }
+    HIP_TRY(c, hipMemcpyAsync(out_tokens, c->gen_y, (size_t)max_new * 4, hipMemcpyDeviceToHost, st));
+    if (trace) HIP_TRY(c, hipMemcpyAsync(trace, c->gen_trace, (size_t)steps * sizeof(llma_step_rec), hipMemcpyDeviceToHost, st));
+    HIP_TRY(c, hipMemcpyAsync(&c->pending_host[seq], c->s.pending + seq, 4, hipMemcpyDeviceToHost, st));
+    HIP_TRY(c, hipStreamSynchronize(st));
+    *n_out = produced;
+    if (n_steps) *n_steps = steps;
+    return LLMA_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// inspection / options
+// ------------------------------------------------------------------------------------------------
+extern "C" int llma_set_logits_dump(llma_ctx *c, float *dev_buf, int32_t capacity_rows) {
+    if (!c) return fail(nullptr, LLMA_E_INVAL, "llma_set_logits_dump: null context");
+    if (dev_buf && capacity_rows < 1) return fail(c, LLMA_E_INVAL, "llma_set_logits_dump: capacity_rows < 1");
+    c->logits_dump = dev_buf;
+    c->dump_rows = dev_buf ? capacity_rows : 0;
+    return LLMA_OK;
+}
+
+extern "C" int llma_set_option(llma_ctx *c, int32_t option, int32_t value) {
+    if (!c) return fail(nullptr, LLMA_E_INVAL, "llma_set_option: null context");
+    switch (option) {
+        case LLMA_OPT_ACT_SPLIT: c->opt_split = value ? 1 : 0; return LLMA_OK;
+        case LLMA_OPT_KERNEL_TIMING: c->opt_timing = value ? 1 : 0; return LLMA_OK;
+        case LLMA_OPT_USE_GRAPH: c->opt_graph = value ? 1 : 0; return LLMA_OK;
+        default: return fail(c, LLMA_E_INVAL, "llma_set_option: unknown option %d", option);
+    }
+}
+
+extern "C" int llma_get_kernel_timing(llma_ctx *c, int64_t *launches, double *total_ms) {
+    if (!c || !launches || !total_ms) return fail(c, LLMA_E_INVAL, "llma_get_kernel_timing: null argument");
+    HIP_TRY(c, hipStreamSynchronize(c->st));
+    double tot = 0.0;
+    for (auto &e : c->events) {
+        float ms = 0.f;
+        HIP_TRY(c, hipEventElapsedTime(&ms, e.a, e.b));
+        tot += ms;
+        (void)hipEventDestroy(e.a);
+        (void)hipEventDestroy(e.b);
+    }
+    *launches = (int64_t)c->events.size();
+    *total_ms = tot;
+    c->events.clear();
+    return LLMA_OK;
+}
