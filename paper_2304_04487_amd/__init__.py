@@ -36,7 +36,7 @@ class LlmaError(RuntimeError):
 
 class ModelCfgC(ctypes.Structure):
     _fields_ = [(n, c_int32) for n in ("n_layers", "d_model", "n_heads", "head_dim", "d_ffn", "vocab",
-                                       "max_seq", "max_batch", "max_k", "dtype")] + \
+                                       "max_seq", "max_batch", "max_k", "dtype", "kv_split")] + \
                [("rms_eps", c_float), ("rope_theta", c_float)]
 
 
@@ -114,7 +114,8 @@ class Context:
     vocab, dtype ("fp32" | "bf16"), rms_eps, rope_theta; `weights` the dict of numpy arrays
     (bf16 as uint16 bit patterns) laid out as llma.h describes."""
 
-    def __init__(self, cfg, weights: dict, max_seq: int, max_batch: int = 1, max_k: int = 16, device="cuda:0"):
+    def __init__(self, cfg, weights: dict, max_seq: int, max_batch: int = 1, max_k: int = 16, device="cuda:0",
+                 kv_split: bool = True):
         import torch
         self._torch = torch
         self.lib = load_library()
@@ -126,7 +127,8 @@ class Context:
         stream = torch.cuda.current_stream(self.device)
         L = len(weights["layers"])
         c = ModelCfgC(L, cfg.d_model, cfg.n_heads, cfg.head_dim, cfg.d_ffn, cfg.vocab, max_seq, max_batch, max_k,
-                      LLMA_DTYPE_BF16 if cfg.dtype == "bf16" else LLMA_DTYPE_F32, cfg.rms_eps, cfg.rope_theta)
+                      LLMA_DTYPE_BF16 if cfg.dtype == "bf16" else LLMA_DTYPE_F32, int(bool(kv_split)),
+                      cfg.rms_eps, cfg.rope_theta)
 
         def dev(a):
             return torch.from_numpy(np.ascontiguousarray(a)).to(self.device)

@@ -24,25 +24,42 @@ __device__ __forceinline__ void split_bf16(float x, bf16_t &hi, bf16_t &lo) {
     hi = f32_to_bf16(x);
     lo = f32_to_bf16(x - bf16_to_f32(hi));
 }
+__device__ __forceinline__ void split4(const float v[4], u32x2 &hi, u32x2 &lo) {
+    bf16_t h[4], l[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) split_bf16(v[r], h[r], l[r]);
+    hi = (u32x2){(uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16)};
+    lo = (u32x2){(uint32_t)l[0] | ((uint32_t)l[1] << 16), (uint32_t)l[2] | ((uint32_t)l[3] << 16)};
+}
 __device__ __forceinline__ f32x4 mfma16x16x32(u32x4 a, u32x4 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
                                                    __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
 // ---- tiled weight layout (bf16) ------------------------------------------------------------
-// A row-major matrix W[N][K] (N % 16 == 0, K % 32 == 0) is stored as N/16 x K/32 blocks of
-// 1 KiB.  Block (ft, ks) holds W[16 ft .. 16 ft+15][32 ks .. 32 ks+31]; inside it lane l of a
-// wavefront owns 16 contiguous bytes: W[16 ft + l%16][32 ks + 8 (l/16) .. +7].  That is the
-// A-operand register image of v_mfma_f32_16x16x32_bf16, so a wavefront fetches one block
-// with a single fully coalesced 16-byte-per-lane load and feeds it to the MFMA unchanged.
+// A row-major matrix W[N][K] (N % 16 == 0, K % 32 == 0) is stored as N/16 x KSp blocks of
+// 1 KiB (KSp >= K/32 k-steps; blocks past K/32 are zero padding).  Block (ft, ks) holds
+// W[16 ft .. 16 ft+15][32 ks .. 32 ks+31]; inside it lane l of a wavefront owns 16 contiguous
+// bytes: W[16 ft + l%16][32 ks + 8 (l/16) .. +7].  That is the A-operand register image of
+// v_mfma_f32_16x16x32_bf16, so a wavefront fetches one block with a single fully coalesced
+// 16-byte-per-lane load and feeds it to the MFMA unchanged.
+//
+// ---- tiled activation layout (bf16) ---------------------------------------------------------
+// Activations X[rows][K] that feed a GEMM are stored as the matching B-operand images, one
+// plane for the hi part and one for the lo part of each value: block (t, ks) of 1 KiB holds rows
+// 16 t .. 16 t+15, columns 32 ks .. +31; lane l owns X[16 t + l%16][32 ks + 8 (l/16) .. +7].
+__host__ __device__ __forceinline__ size_t xtile_off(int row, int col, int KSp) {
+    return ((size_t)((row >> 4) * KSp + (col >> 5)) * 64 + (size_t)(((col & 31) >> 3) * 16 + (row & 15))) * 8 + (col & 7);
+}
 
-// ---- KV cache layout (bf16), per (slot, head): max_seq x head_dim elements -------------------
+// ---- KV cache layout (bf16), per (slot, head): max_seq x head_dim elements per plane ---------
 // K: groups of 16 positions; group g16 holds head_dim/32 blocks of 1 KiB, block s = the
 //    A-operand image of K[16 g16 .. +15][32 s .. 32 s+31] (lane l: position l%16, dims 8(l/16)..).
 // V: groups of 32 positions; group g32 holds head_dim/16 blocks of 1 KiB, block dt = the
 //    A-operand image of V^T[16 dt .. +15][32 positions], where slot (kb, j) of the 32-wide
 //    reduction axis is position  16 (j/4) + 4 kb + j%4  of the group: exactly the order in
 //    which the score MFMAs leave probabilities in a lane's registers.
+// With kv_split the cache has a second plane of the same shape holding the lo parts.
 __host__ __device__ __forceinline__ size_t kcache_off(int pos, int c, int dh) {
     int g16 = pos >> 4, i = pos & 15, s = c >> 5, kb = (c & 31) >> 3, j = c & 7;
     return (size_t)g16 * (16 * dh) + (size_t)s * 512 + (size_t)(kb * 16 + i) * 8 + j;
@@ -54,25 +71,55 @@ __host__ __device__ __forceinline__ size_t vcache_off(int pos, int c, int dh) {
 }
 
 // ---- launcher argument structs --------------------------------------------------------------
-enum { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LMHEAD = 3 };
+enum { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LMHEAD = 3, EPI_QKV = 4 };
 
-struct GemmArgs {
-    const void *W;          // tiled bf16 weights, or row-major fp32 weights
-    const void *Xhi;        // activations [rows_pad][K]: bf16 hi part, or fp32
-    const void *Xlo;        // bf16 lo part (bf16 path with split), else unused
-    int N, K;               // logical output features (for SWIGLU: d_ffn), reduction length
-    int rows;               // valid rows
+// how one weight matrix is cut into work: a function of its shape only (never of the row count)
+struct GemmPlan {
+    int N, K;        // logical shape (SWIGLU: N = d_ffn, the matrix has 2N rows)
+    int KSp;         // k-steps per feature tile incl. zero padding, = S * KSS
+    int S, KSS;      // K slices and k-steps per slice
+    int G;           // workgroups per slice
+    int tasks;       // feature tiles (SWIGLU: gate/up tile pairs)
+};
+
+struct GemmArgs {          // bf16 path (fields marked f32 are used by the fp32 kernels only)
+    const void *W;         // tiled bf16 weights, or row-major fp32 weights
+    const void *Xhi;       // bf16: tiled activations, hi plane; f32: row-major [rows][K]
+    const void *Xlo;       // bf16: lo plane
+    GemmPlan plan;
+    int N, K;              // f32: logical output features, reduction length
+    int rows;              // valid rows
     int epi;
-    float *out;             // STORE: [rows][N] fp32; RESID: h[rows][N] += ; LMHEAD: optional logits dump (may be null)
-    void *act_hi, *act_lo;  // SWIGLU: [rows_pad][N] bf16 hi/lo, or fp32 in act_hi
-    float *pval; int *pidx; // LMHEAD: per-row partial arg max [rows][n_part]
-    int n_part;
-    int split;              // use Xlo
+    int split;             // use Xlo
+    float *partial;        // [tasks][S][tiles][NT][64] f32x4 partial sums
+    int *ticket;           // [tasks], zero between launches
+    // inputs of the epilogues
+    const float *ssq_in;   // [rows][ssq_tiles] sums of squares of the producer's residual rows
+    int ssq_tiles;         //   rstd[row] = rsqrt(sum / (16 ssq_tiles) + eps)
+    float eps;
+    // EPI_STORE (f32) / EPI_RESID / EPI_LMHEAD
+    float *out;            // STORE: [rows][N]; RESID: h[rows][N] += ; LMHEAD: optional logits dump (may be null)
+    // EPI_RESID: prepares the next RMSNorm'd GEMM input
+    const float *gain;     // [N] gains of the next norm
+    void *nx_hi, *nx_lo;   // tiled planes over N columns with nx_KSp k-steps per row tile: (h * gain) hi / lo
+    int nx_KSp;
+    float *ssq_out;        // [rows][N/16]
+    // EPI_SWIGLU
+    void *act_hi, *act_lo; // tiled planes over d_ffn (KSp of the down projection) ; f32: row-major in act_hi
+    int act_KSp;
+    // EPI_LMHEAD
+    float *pval; int *pidx; int n_part;
+    // EPI_QKV: rotate, write q (tiled planes over d_model), append k, v to the cache
+    const int *row_pos, *row_slot;
+    const float *cs;       // [max_seq][dh/2][2]
+    void *q_hi, *q_lo;
+    void *k_hi, *k_lo, *v_hi, *v_lo;   // this layer's cache planes (lo may be null)
+    int H, dh, max_seq;
 };
 
 struct AttnArgs {
-    const void *Q;          // [R][d_model] bf16 (rotated) or fp32
-    const void *Kc, *Vc;    // this layer's cache base
+    const void *Qhi, *Qlo;  // bf16: tiled planes over d_model; f32: Qhi = [R][d_model]
+    const void *Khi, *Klo, *Vhi, *Vlo;   // this layer's cache (lo null without kv_split); f32: Khi, Vhi
     const int *T;           // [max_batch] device lengths before the step
     const int *batch_slots; // [n_seqs]
     int n_seqs, m;          // rows per sequence
@@ -80,8 +127,8 @@ struct AttnArgs {
     int n_chunks;           // launched chunks (upper bound over the batch)
     float scale;
     float *po, *pm, *pl;    // partials
-    void *out_hi, *out_lo;  // [R_pad][d_model] bf16 hi/lo or fp32
-    int split;
+    void *out_hi, *out_lo;  // bf16: tiled planes over d_model (out_KSp k-steps per row tile); f32: out_hi = [R][d_model]
+    int out_KSp;
 };
 
 #define ATTN_CHUNK 256      // key positions per workgroup (4 waves x 2 groups of 32)

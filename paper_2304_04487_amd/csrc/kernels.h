@@ -3,9 +3,13 @@
 #include "common.h"
 
 // ---- bf16 path (kernels_bf16.hip)
-void launch_pack_weight(const void *src, void *dst, int N, int K, hipStream_t st);
-void launch_kv_import_bf16(const void *k, const void *v, void *kc, void *vc, int H, int len, int dh,
+GemmPlan make_gemm_plan(int N, int K, int tiles_per_task);
+size_t gemm_bf16_lds_bytes(const GemmPlan &p, int nt, int split);
+void launch_pack_weight(const void *src, void *dst, int N, int K, int KSp, int rope_dh, int d, hipStream_t st);
+void launch_kv_import_bf16(const void *k, const void *v, void *kh, void *kl, void *vh, void *vl, int H, int len, int dh,
                            int max_seq, hipStream_t st);
+void launch_embed_prep_bf16(const void *embed, const int *row_tok, const float *gain, float *h, void *nx_hi, void *nx_lo,
+                            float *ssq_out, int R, int d, int KSp, hipStream_t st);
 void launch_gemm_bf16(const GemmArgs &a, hipStream_t st);
 void launch_attn_bf16(const AttnArgs &a, hipStream_t st);
 
@@ -38,14 +42,13 @@ void launch_setup_step_rows(const StepState &s, int n_seqs, int m, int max_k, hi
 // rows of a prefill chunk for one slot: tokens prompt[off .. off+m), pos = T[slot] + j
 void launch_setup_prefill_rows(const StepState &s, const int *prompt_dev, int off, int m, int slot, hipStream_t st);
 void launch_advance_T(const StepState &s, int slot, int by, hipStream_t st);
-// h[r][:] = embed[row_tok[r]][:]  (embed bf16 or fp32 -> fp32)
-void launch_embed(const void *embed, int is_bf16, const int *row_tok, float *h, int R, int d, hipStream_t st);
-// x = RMSNorm(h; g): bf16 hi/lo (is_bf16) or fp32 into out_hi
-void launch_rmsnorm(const float *h, const float *g, float eps, void *out_hi, void *out_lo, int is_bf16,
-                    int R, int d, hipStream_t st);
-// rotate q, k of every row at its position, write q, append k and v to the cache
-void launch_rope_kv(const float *qkv, const StepState &s, const float *cs_table, void *q_out, void *kc, void *vc,
-                    int is_bf16, int R, int H, int dh, int max_seq, hipStream_t st);
+// fp32 path: h[r][:] = embed[row_tok[r]][:]
+void launch_embed_f32(const float *embed, const int *row_tok, float *h, int R, int d, hipStream_t st);
+// fp32 path: x = RMSNorm(h; g)
+void launch_rmsnorm_f32(const float *h, const float *g, float eps, float *out, int R, int d, hipStream_t st);
+// fp32 path: rotate q, k of every row at its position, write q, append k and v to the cache
+void launch_rope_kv_f32(const float *qkv, const StepState &s, const float *cs_table, float *q_out, float *kc, float *vc,
+                        int R, int H, int dh, int max_seq, hipStream_t st);
 // final arg max over the per-row partials, then prefix accept + KV truncate + bookkeeping
 void launch_argmax_accept(const float *pval, const int *pidx, int n_part, const StepState &s, int n_seqs, int m,
                           int max_k, const GenState *gen /*device copy or null*/, hipStream_t st);

@@ -97,11 +97,11 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(AttnArgs a) {
     const int slot = a.batch_slots[b];
     const int pos = a.T[slot] + j;
     const int d_model = a.H * DH;
-    const float *q = (const float *)a.Q + (size_t)r * d_model + h * DH;
+    const float *q = (const float *)a.Qhi + (size_t)r * d_model + h * DH;
     for (int c = lane; c < DH; c += 64) qs[c] = q[c];
     __syncthreads();
     const size_t head_base = ((size_t)slot * a.H + h) * (size_t)a.max_seq * DH;
-    const float *kc = (const float *)a.Kc + head_base, *vc = (const float *)a.Vc + head_base;
+    const float *kc = (const float *)a.Khi + head_base, *vc = (const float *)a.Vhi + head_base;
     float mx = LLMA_NEG_INF, l = 0.f, acc[DH];
 #pragma unroll
     for (int c = 0; c < DH; ++c) acc[c] = 0.f;

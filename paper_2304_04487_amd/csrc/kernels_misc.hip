@@ -1,5 +1,5 @@
-// Small kernels around the GEMMs and attention: row set-up, embedding gather, RMSNorm,
-// RoPE + KV append, the vocabulary arg max with the prefix-accept / KV-truncate decision
+// Small kernels around the GEMMs and attention: row set-up, the fp32 path's embedding gather /
+// RMSNorm / RoPE + KV append, the vocabulary arg max with the prefix-accept / KV-truncate decision
 // (paper: Algorithm 1, the compare loop after the verification forward), and the n-gram
 // trigger scan over the reference (paper: Method, the match that starts a copy).
 #include "common.h"
@@ -43,23 +43,20 @@ void launch_advance_T(const StepState &s, int slot, int by, hipStream_t st) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// embedding gather
+// fp32 path: embedding gather, RMSNorm, RoPE + KV append as separate small kernels
 // ---------------------------------------------------------------------------------------------
-__global__ void embed_kernel(const void *embed, int is_bf16, const int *row_tok, float *h, int d) {
+__global__ void embed_f32_kernel(const float *embed, const int *row_tok, float *h, int d) {
     int r = blockIdx.x;
     size_t base = (size_t)row_tok[r] * d;
-    for (int c = threadIdx.x; c < d; c += blockDim.x)
-        h[(size_t)r * d + c] = is_bf16 ? bf16_to_f32(((const bf16_t *)embed)[base + c]) : ((const float *)embed)[base + c];
+    for (int c = threadIdx.x; c < d; c += blockDim.x) h[(size_t)r * d + c] = embed[base + c];
 }
-void launch_embed(const void *embed, int is_bf16, const int *row_tok, float *h, int R, int d, hipStream_t st) {
-    hipLaunchKernelGGL(embed_kernel, dim3(R), dim3(256), 0, st, embed, is_bf16, row_tok, h, d);
+void launch_embed_f32(const float *embed, const int *row_tok, float *h, int R, int d, hipStream_t st) {
+    hipLaunchKernelGGL(embed_f32_kernel, dim3(R), dim3(256), 0, st, embed, row_tok, h, d);
 }
 
-// ---------------------------------------------------------------------------------------------
-// RMSNorm: one workgroup per row; fixed summation order (thread-strided, butterfly, wave order)
-// ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const float *__restrict__ h, const float *__restrict__ g, float eps,
-                                                      void *out_hi, void *out_lo, int is_bf16, int d) {
+// one workgroup per row; fixed summation order (thread-strided, butterfly, wave order)
+__global__ __launch_bounds__(256) void rmsnorm_f32_kernel(const float *__restrict__ h, const float *__restrict__ g, float eps,
+                                                          float *__restrict__ out, int d) {
     __shared__ float part[4];
     const int r = blockIdx.x;
     const float *x = h + (size_t)r * d;
@@ -71,29 +68,16 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float *__restrict__ 
     __syncthreads();
     float tot = ((part[0] + part[1]) + part[2]) + part[3];
     float rstd = 1.0f / sqrtf(tot / (float)d + eps);
-    for (int c = threadIdx.x; c < d; c += 256) {
-        float v = x[c] * rstd * g[c];
-        if (is_bf16) {
-            bf16_t hi, lo;
-            split_bf16(v, hi, lo);
-            ((bf16_t *)out_hi)[(size_t)r * d + c] = hi;
-            ((bf16_t *)out_lo)[(size_t)r * d + c] = lo;
-        } else {
-            ((float *)out_hi)[(size_t)r * d + c] = v;
-        }
-    }
+    for (int c = threadIdx.x; c < d; c += 256) out[(size_t)r * d + c] = x[c] * rstd * g[c];
 }
-void launch_rmsnorm(const float *h, const float *g, float eps, void *out_hi, void *out_lo, int is_bf16,
-                    int R, int d, hipStream_t st) {
-    hipLaunchKernelGGL(rmsnorm_kernel, dim3(R), dim3(256), 0, st, h, g, eps, out_hi, out_lo, is_bf16, d);
+void launch_rmsnorm_f32(const float *h, const float *g, float eps, float *out, int R, int d, hipStream_t st) {
+    hipLaunchKernelGGL(rmsnorm_f32_kernel, dim3(R), dim3(256), 0, st, h, g, eps, out, d);
 }
 
-// ---------------------------------------------------------------------------------------------
-// RoPE + KV append.  grid (rows, heads), head_dim/2 threads: thread i rotates the pair
-// (i, i + head_dim/2) of q and k by angle pos * theta^(-2i/head_dim) (table built on the host).
-// ---------------------------------------------------------------------------------------------
-__global__ void rope_kv_kernel(const float *__restrict__ qkv, StepState s, const float *__restrict__ cs,
-                               void *q_out, void *kc, void *vc, int is_bf16, int H, int dh, int max_seq) {
+// grid (rows, heads), head_dim/2 threads: thread i rotates the pair (i, i + head_dim/2) of q and k
+// by angle pos * theta^(-2i/head_dim) (table built on the host)
+__global__ void rope_kv_f32_kernel(const float *__restrict__ qkv, StepState s, const float *__restrict__ cs,
+                                   float *q_out, float *kc, float *vc, int H, int dh, int max_seq) {
     const int r = blockIdx.x, hh = blockIdx.y, i = threadIdx.x;
     const int half = dh >> 1, d = H * dh;
     const int pos = s.row_pos[r], slot = s.row_slot[r];
@@ -102,30 +86,19 @@ __global__ void rope_kv_kernel(const float *__restrict__ qkv, StepState s, const
     const float q1 = row[hh * dh + i], q2 = row[hh * dh + i + half];
     const float k1 = row[d + hh * dh + i], k2 = row[d + hh * dh + i + half];
     const float v1 = row[2 * d + hh * dh + i], v2 = row[2 * d + hh * dh + i + half];
-    const float qa = q1 * c - q2 * sn, qb = q2 * c + q1 * sn;
-    const float ka = k1 * c - k2 * sn, kb = k2 * c + k1 * sn;
     const size_t head_base = ((size_t)slot * H + hh) * (size_t)max_seq * dh;
-    if (is_bf16) {
-        bf16_t *q = (bf16_t *)q_out + (size_t)r * d + hh * dh;
-        q[i] = f32_to_bf16(qa);
-        q[i + half] = f32_to_bf16(qb);
-        bf16_t *kp = (bf16_t *)kc + head_base, *vp = (bf16_t *)vc + head_base;
-        kp[kcache_off(pos, i, dh)] = f32_to_bf16(ka);
-        kp[kcache_off(pos, i + half, dh)] = f32_to_bf16(kb);
-        vp[vcache_off(pos, i, dh)] = f32_to_bf16(v1);
-        vp[vcache_off(pos, i + half, dh)] = f32_to_bf16(v2);
-    } else {
-        float *q = (float *)q_out + (size_t)r * d + hh * dh;
-        q[i] = qa;
-        q[i + half] = qb;
-        float *kp = (float *)kc + head_base + (size_t)pos * dh, *vp = (float *)vc + head_base + (size_t)pos * dh;
-        kp[i] = ka; kp[i + half] = kb;
-        vp[i] = v1; vp[i + half] = v2;
-    }
+    float *q = q_out + (size_t)r * d + hh * dh;
+    q[i] = q1 * c - q2 * sn;
+    q[i + half] = q2 * c + q1 * sn;
+    float *kp = kc + head_base + (size_t)pos * dh, *vp = vc + head_base + (size_t)pos * dh;
+    kp[i] = k1 * c - k2 * sn;
+    kp[i + half] = k2 * c + k1 * sn;
+    vp[i] = v1;
+    vp[i + half] = v2;
 }
-void launch_rope_kv(const float *qkv, const StepState &s, const float *cs_table, void *q_out, void *kc, void *vc,
-                    int is_bf16, int R, int H, int dh, int max_seq, hipStream_t st) {
-    hipLaunchKernelGGL(rope_kv_kernel, dim3(R, H), dim3(dh / 2), 0, st, qkv, s, cs_table, q_out, kc, vc, is_bf16, H, dh, max_seq);
+void launch_rope_kv_f32(const float *qkv, const StepState &s, const float *cs_table, float *q_out, float *kc, float *vc,
+                        int R, int H, int dh, int max_seq, hipStream_t st) {
+    hipLaunchKernelGGL(rope_kv_f32_kernel, dim3(R, H), dim3(dh / 2), 0, st, qkv, s, cs_table, q_out, kc, vc, H, dh, max_seq);
 }
 
 // ---------------------------------------------------------------------------------------------

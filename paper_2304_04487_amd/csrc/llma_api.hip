@@ -9,6 +9,7 @@
 #include <string.h>
 
 #include <string>
+#include <utility>
 #include <vector>
 
 #include "../../include/llma.h"
@@ -34,16 +35,21 @@ struct llma_ctx {
     float *final_norm = nullptr;
     std::vector<void *> wqkv, wo, wgu, wd;
     std::vector<float *> n1, n2;
-    // KV cache per layer: [max_batch][H][max_seq][dh]
-    std::vector<void *> kc, vc;
+    // KV cache per layer: [max_batch][H][max_seq][dh]; bf16 with kv_split: a second (lo) plane
+    std::vector<void *> kc, vc, kc_lo, vc_lo;
     float *cs_table = nullptr;
+    bool kv_split = false;
 
-    // scratch for up to Rmax rows
+    // scratch for up to Rmax rows.  bf16: x/q/att/act are tiled hi/lo planes; fp32: row-major in *_hi
     int Rmax = 0;
     float *h = nullptr, *qkv = nullptr;
-    void *xhi = nullptr, *xlo = nullptr, *q = nullptr, *att_hi = nullptr, *att_lo = nullptr, *act_hi = nullptr, *act_lo = nullptr;
+    void *xhi = nullptr, *xlo = nullptr, *q = nullptr, *q_lo = nullptr, *att_hi = nullptr, *att_lo = nullptr, *act_hi = nullptr, *act_lo = nullptr;
     float *po = nullptr, *pm = nullptr, *pl = nullptr;
     int nc_max = 0;
+    // bf16 GEMM work division, partial-sum scratch, tickets, per-tile sums of squares
+    GemmPlan plan_qkv{}, plan_o{}, plan_gu{}, plan_down{}, plan_lm{};
+    float *partial = nullptr, *ssq = nullptr;
+    int *ticket = nullptr;
     float *pval = nullptr;
     int *pidx = nullptr;
     int n_part = 0;
@@ -125,11 +131,16 @@ static int check_cfg(const llma_model_cfg *g) {
     return LLMA_OK;
 }
 
-static int take_matrix(llma_ctx *c, void **dst, const void *src, int N, int K) {
-    size_t bytes = (size_t)N * K * (c->bf16 ? 2 : 4);
-    ALLOC(c, *dst, bytes);
-    if (c->bf16) launch_pack_weight(src, *dst, N, K, c->st);
-    else HIP_TRY(c, hipMemcpyAsync(*dst, src, bytes, hipMemcpyDeviceToDevice, c->st));
+// copies one matrix into context-owned memory: fp32 as is, bf16 re-tiled (N rows, K padded to KSp k-steps)
+static int take_matrix(llma_ctx *c, void **dst, const void *src, int N, int K, int KSp, int rope_dh) {
+    if (c->bf16) {
+        ALLOC(c, *dst, (size_t)(N / 16) * KSp * 1024);
+        launch_pack_weight(src, *dst, N, K, KSp, rope_dh, c->cfg.d_model, c->st);
+    } else {
+        size_t bytes = (size_t)N * K * 4;
+        ALLOC(c, *dst, bytes);
+        HIP_TRY(c, hipMemcpyAsync(*dst, src, bytes, hipMemcpyDeviceToDevice, c->st));
+    }
     return LLMA_OK;
 }
 
@@ -137,22 +148,33 @@ static int create_impl(llma_ctx *c, const llma_weights *w) {
     const llma_model_cfg &g = c->cfg;
     const int L = g.n_layers, d = g.d_model, F = g.d_ffn, V = g.vocab, H = g.n_heads, dh = g.head_dim;
     const size_t es = c->bf16 ? 2 : 4;
+    if (c->bf16) {
+        c->plan_qkv = make_gemm_plan(3 * d, d, 1);
+        c->plan_o = make_gemm_plan(d, d, 1);
+        c->plan_gu = make_gemm_plan(F, d, 2);
+        c->plan_down = make_gemm_plan(d, F, 1);
+        c->plan_lm = make_gemm_plan(V, d, 1);
+        const GemmPlan *pl[] = {&c->plan_qkv, &c->plan_o, &c->plan_gu, &c->plan_down, &c->plan_lm};
+        for (const GemmPlan *p : pl)
+            if (gemm_bf16_lds_bytes(*p, 1, 1) > 150 * 1024) return fail(c, LLMA_E_INVAL, "matrix [%d x %d] does not fit the GEMM's LDS slice", p->N, p->K);
+    }
     // ---- weights
     ALLOC(c, c->embed, (size_t)V * d * es);
     HIP_TRY(c, hipMemcpyAsync(c->embed, w->embed, (size_t)V * d * es, hipMemcpyDeviceToDevice, c->st));
-    int rc = take_matrix(c, &c->lm_head, w->lm_head, V, d);
+    int rc = take_matrix(c, &c->lm_head, w->lm_head, V, d, c->plan_lm.KSp, 0);
     if (rc) return rc;
     ALLOC(c, c->final_norm, d * 4);
     HIP_TRY(c, hipMemcpyAsync(c->final_norm, w->final_norm, d * 4, hipMemcpyDeviceToDevice, c->st));
     c->wqkv.assign(L, nullptr); c->wo.assign(L, nullptr); c->wgu.assign(L, nullptr); c->wd.assign(L, nullptr);
-    c->n1.assign(L, nullptr); c->n2.assign(L, nullptr); c->kc.assign(L, nullptr); c->vc.assign(L, nullptr);
+    c->n1.assign(L, nullptr); c->n2.assign(L, nullptr);
+    c->kc.assign(L, nullptr); c->vc.assign(L, nullptr); c->kc_lo.assign(L, nullptr); c->vc_lo.assign(L, nullptr);
     for (int l = 0; l < L; ++l) {
         if (!w->wqkv[l] || !w->wo[l] || !w->wgu[l] || !w->wdown[l] || !w->norm1[l] || !w->norm2[l])
             return fail(c, LLMA_E_INVAL, "null weight pointer in layer %d", l);
-        if ((rc = take_matrix(c, &c->wqkv[l], w->wqkv[l], 3 * d, d))) return rc;
-        if ((rc = take_matrix(c, &c->wo[l], w->wo[l], d, d))) return rc;
-        if ((rc = take_matrix(c, &c->wgu[l], w->wgu[l], 2 * F, d))) return rc;
-        if ((rc = take_matrix(c, &c->wd[l], w->wdown[l], d, F))) return rc;
+        if ((rc = take_matrix(c, &c->wqkv[l], w->wqkv[l], 3 * d, d, c->plan_qkv.KSp, dh))) return rc;
+        if ((rc = take_matrix(c, &c->wo[l], w->wo[l], d, d, c->plan_o.KSp, 0))) return rc;
+        if ((rc = take_matrix(c, &c->wgu[l], w->wgu[l], 2 * F, d, c->plan_gu.KSp, 0))) return rc;
+        if ((rc = take_matrix(c, &c->wd[l], w->wdown[l], d, F, c->plan_down.KSp, 0))) return rc;
         ALLOC(c, c->n1[l], d * 4);
         ALLOC(c, c->n2[l], d * 4);
         HIP_TRY(c, hipMemcpyAsync(c->n1[l], w->norm1[l], d * 4, hipMemcpyDeviceToDevice, c->st));
@@ -165,6 +187,12 @@ static int create_impl(llma_ctx *c, const llma_weights *w) {
         ALLOC(c, c->vc[l], kv_bytes);
         HIP_TRY(c, hipMemsetAsync(c->kc[l], 0, kv_bytes, c->st));
         HIP_TRY(c, hipMemsetAsync(c->vc[l], 0, kv_bytes, c->st));
+        if (c->kv_split) {
+            ALLOC(c, c->kc_lo[l], kv_bytes);
+            ALLOC(c, c->vc_lo[l], kv_bytes);
+            HIP_TRY(c, hipMemsetAsync(c->kc_lo[l], 0, kv_bytes, c->st));
+            HIP_TRY(c, hipMemsetAsync(c->vc_lo[l], 0, kv_bytes, c->st));
+        }
     }
     // ---- rotary table: cos/sin(pos * theta^(-2i/dh)) in double, stored fp32
     {
@@ -185,26 +213,39 @@ static int create_impl(llma_ctx *c, const llma_weights *w) {
     const int m_max = g.max_k + 1;
     c->Rmax = g.max_batch * m_max;
     if (c->Rmax < PREFILL_ROWS) c->Rmax = PREFILL_ROWS;
-    const size_t Rp = (size_t)c->Rmax + 48;                  // slack: the GEMM reads whole 16-row tiles
-    ALLOC(c, c->h, Rp * d * 4);
-    ALLOC(c, c->qkv, Rp * 3 * d * 4);
-    ALLOC(c, c->xhi, Rp * d * es);
-    ALLOC(c, c->xlo, Rp * d * es);
-    ALLOC(c, c->q, Rp * d * es);
-    ALLOC(c, c->att_hi, Rp * d * es);
-    ALLOC(c, c->att_lo, Rp * d * es);
-    ALLOC(c, c->act_hi, Rp * F * es);
-    ALLOC(c, c->act_lo, Rp * F * es);
-    void *zero_these[] = {c->h, c->qkv, c->xhi, c->xlo, c->q, c->att_hi, c->att_lo, c->act_hi, c->act_lo};
-    size_t zero_bytes[] = {Rp * d * 4, Rp * 3 * d * 4, Rp * d * es, Rp * d * es, Rp * d * es, Rp * d * es, Rp * d * es, Rp * F * es, Rp * F * es};
-    for (int i = 0; i < 9; ++i) HIP_TRY(c, hipMemsetAsync(zero_these[i], 0, zero_bytes[i], c->st));
+    const size_t Rp = ((size_t)c->Rmax + 15) / 16 * 16 + 48;     // slack: the GEMM reads whole 16-row tiles
+    std::vector<std::pair<void *, size_t>> zero;
+    auto zalloc = [&](void **p, size_t bytes) -> int { int r = dev_alloc(c, p, bytes); if (r == LLMA_OK) zero.push_back({*p, bytes}); return r; };
+    if ((rc = zalloc((void **)&c->h, Rp * d * 4))) return rc;
     if (c->bf16) {
+        const size_t Tt = Rp / 16;                                // row tiles
+        const size_t x_bytes = Tt * c->plan_qkv.KSp * 1024, q_bytes = Tt * (d / 32) * 1024, act_bytes = Tt * c->plan_down.KSp * 1024;
+        if ((rc = zalloc(&c->xhi, x_bytes)) || (rc = zalloc(&c->xlo, x_bytes)) || (rc = zalloc(&c->q, q_bytes)) ||
+            (rc = zalloc(&c->q_lo, q_bytes)) || (rc = zalloc(&c->att_hi, x_bytes)) || (rc = zalloc(&c->att_lo, x_bytes)) ||
+            (rc = zalloc(&c->act_hi, act_bytes)) || (rc = zalloc(&c->act_lo, act_bytes)))
+            return rc;
+        if ((rc = zalloc((void **)&c->ssq, Rp * (d / 16) * 4))) return rc;
+        size_t part = 0;
+        int max_tasks = 0;
+        const GemmPlan *pl[] = {&c->plan_qkv, &c->plan_o, &c->plan_gu, &c->plan_down, &c->plan_lm};
+        for (const GemmPlan *p : pl) {
+            const size_t b = (size_t)p->tasks * p->S * (p == &c->plan_gu ? 2 : 1) * 3 * 1024;
+            if (b > part) part = b;
+            if (p->tasks > max_tasks) max_tasks = p->tasks;
+        }
+        ALLOC(c, c->partial, part);
+        if ((rc = zalloc((void **)&c->ticket, (size_t)max_tasks * 4))) return rc;
         c->nc_max = (g.max_seq + ATTN_CHUNK - 1) / ATTN_CHUNK;
         const size_t np = (size_t)g.max_batch * H * c->nc_max * 48;
         ALLOC(c, c->po, np * dh * 4);
         ALLOC(c, c->pm, np * 4);
         ALLOC(c, c->pl, np * 4);
+    } else {
+        if ((rc = zalloc((void **)&c->qkv, Rp * 3 * d * 4)) || (rc = zalloc(&c->xhi, Rp * d * 4)) || (rc = zalloc(&c->q, Rp * d * 4)) ||
+            (rc = zalloc(&c->att_hi, Rp * d * 4)) || (rc = zalloc(&c->act_hi, Rp * F * 4)))
+            return rc;
     }
+    for (auto &z : zero) HIP_TRY(c, hipMemsetAsync(z.first, 0, z.second, c->st));
     c->n_part = c->bf16 ? V / 16 : V;
     ALLOC(c, c->pval, (size_t)c->Rmax * c->n_part * 4);
     ALLOC(c, c->pidx, (size_t)c->Rmax * c->n_part * 4);
@@ -225,6 +266,8 @@ static int create_impl(llma_ctx *c, const llma_weights *w) {
     HIP_TRY(c, hipMemsetAsync(s.T, 0, g.max_batch * 4, c->st));
     HIP_TRY(c, hipMemsetAsync(s.pending, 0xFF, g.max_batch * 4, c->st));
     HIP_TRY(c, hipMemsetAsync(s.keff, 0, g.max_batch * 4, c->st));
+    HIP_TRY(c, hipMemsetAsync(s.row_pos, 0, Rp * 4, c->st));
+    HIP_TRY(c, hipMemsetAsync(s.row_slot, 0, Rp * 4, c->st));
     ALLOC(c, c->gen_dev, sizeof(GenState));
     ALLOC(c, c->gen_counters, 4 * 4);
     c->T_host.assign(g.max_batch, 0);
@@ -247,6 +290,7 @@ extern "C" int llma_create(const llma_model_cfg *cfg, const llma_weights *w, voi
     c->cfg = *cfg;
     c->st = (hipStream_t)hip_stream;
     c->bf16 = cfg->dtype == LLMA_DTYPE_BF16;
+    c->kv_split = c->bf16 && cfg->kv_split != 0;
     rc = create_impl(c, w);
     if (rc) {
         std::string e = c->err;
@@ -273,55 +317,101 @@ extern "C" int64_t llma_device_bytes(const llma_ctx *c) { return c ? c->dev_byte
 // ------------------------------------------------------------------------------------------------
 // the forward over the rows described by ctx->s.row_* (paper: Eq. 3)
 // ------------------------------------------------------------------------------------------------
-static int forward(llma_ctx *c, int n_seqs, int m, int t_max, bool lm_head) {
+static int forward_f32(llma_ctx *c, int n_seqs, int m, bool lm_head) {
     const llma_model_cfg &g = c->cfg;
     const int d = g.d_model, F = g.d_ffn, V = g.vocab, H = g.n_heads, dh = g.head_dim, L = g.n_layers;
     const int R = n_seqs * m;
-    const int isb = c->bf16 ? 1 : 0;
     hipStream_t st = c->st;
-    launch_embed(c->embed, isb, c->s.row_tok, c->h, R, d, st);
+    launch_embed_f32((const float *)c->embed, c->s.row_tok, c->h, R, d, st);
     GemmArgs ga{};
-    ga.split = c->bf16 && c->opt_split;
     ga.rows = R;
     AttnArgs aa{};
-    aa.Q = c->q; aa.T = c->s.T; aa.batch_slots = c->s.batch_slots; aa.n_seqs = n_seqs; aa.m = m; aa.H = H; aa.dh = dh;
-    aa.max_seq = g.max_seq; aa.n_chunks = (t_max + m + ATTN_CHUNK - 1) / ATTN_CHUNK; aa.scale = 1.0f / sqrtf((float)dh);
-    aa.po = c->po; aa.pm = c->pm; aa.pl = c->pl; aa.out_hi = c->att_hi; aa.out_lo = c->att_lo;
+    aa.Qhi = c->q; aa.T = c->s.T; aa.batch_slots = c->s.batch_slots; aa.n_seqs = n_seqs; aa.m = m; aa.H = H; aa.dh = dh;
+    aa.max_seq = g.max_seq; aa.scale = 1.0f / sqrtf((float)dh); aa.out_hi = c->att_hi;
     for (int l = 0; l < L; ++l) {
-        launch_rmsnorm(c->h, c->n1[l], g.rms_eps, c->xhi, c->xlo, isb, R, d, st);
-        ga.W = c->wqkv[l]; ga.Xhi = c->xhi; ga.Xlo = c->xlo; ga.N = 3 * d; ga.K = d; ga.epi = EPI_STORE; ga.out = c->qkv;
-        isb ? launch_gemm_bf16(ga, st) : launch_gemm_f32(ga, st);
-        launch_rope_kv(c->qkv, c->s, c->cs_table, c->q, c->kc[l], c->vc[l], isb, R, H, dh, g.max_seq, st);
-        aa.Kc = c->kc[l]; aa.Vc = c->vc[l];
-        isb ? launch_attn_bf16(aa, st) : launch_attn_f32(aa, st);
-        ga.W = c->wo[l]; ga.Xhi = c->att_hi; ga.Xlo = c->att_lo; ga.N = d; ga.K = d; ga.epi = EPI_RESID; ga.out = c->h;
-        isb ? launch_gemm_bf16(ga, st) : launch_gemm_f32(ga, st);
-        launch_rmsnorm(c->h, c->n2[l], g.rms_eps, c->xhi, c->xlo, isb, R, d, st);
-        ga.W = c->wgu[l]; ga.Xhi = c->xhi; ga.Xlo = c->xlo; ga.N = F; ga.K = d; ga.epi = EPI_SWIGLU; ga.out = nullptr;
-        ga.act_hi = c->act_hi; ga.act_lo = c->act_lo;
-        if (c->opt_timing) {
+        launch_rmsnorm_f32(c->h, c->n1[l], g.rms_eps, (float *)c->xhi, R, d, st);
+        ga.W = c->wqkv[l]; ga.Xhi = c->xhi; ga.N = 3 * d; ga.K = d; ga.epi = EPI_STORE; ga.out = c->qkv;
+        launch_gemm_f32(ga, st);
+        launch_rope_kv_f32(c->qkv, c->s, c->cs_table, (float *)c->q, (float *)c->kc[l], (float *)c->vc[l], R, H, dh, g.max_seq, st);
+        aa.Khi = c->kc[l]; aa.Vhi = c->vc[l];
+        launch_attn_f32(aa, st);
+        ga.W = c->wo[l]; ga.Xhi = c->att_hi; ga.N = d; ga.K = d; ga.epi = EPI_RESID; ga.out = c->h;
+        launch_gemm_f32(ga, st);
+        launch_rmsnorm_f32(c->h, c->n2[l], g.rms_eps, (float *)c->xhi, R, d, st);
+        ga.W = c->wgu[l]; ga.Xhi = c->xhi; ga.N = F; ga.K = d; ga.epi = EPI_SWIGLU; ga.out = nullptr; ga.act_hi = c->act_hi;
+        launch_gemm_f32(ga, st);
+        ga.W = c->wd[l]; ga.Xhi = c->act_hi; ga.N = d; ga.K = F; ga.epi = EPI_RESID; ga.out = c->h; ga.act_hi = nullptr;
+        launch_gemm_f32(ga, st);
+    }
+    if (lm_head) {
+        launch_rmsnorm_f32(c->h, c->final_norm, g.rms_eps, (float *)c->xhi, R, d, st);
+        ga.W = c->lm_head; ga.Xhi = c->xhi; ga.N = V; ga.K = d; ga.epi = EPI_LMHEAD;
+        ga.out = c->logits_dump; ga.pval = c->pval; ga.pidx = c->pidx; ga.n_part = c->n_part;
+        launch_gemm_f32(ga, st);
+    }
+    HIP_TRY(c, hipGetLastError());
+    return LLMA_OK;
+}
+
+// bf16: per layer  QKV GEMM (+RMSNorm scale, RoPE, KV append) -> attention -> O GEMM (+residual,
+// next-norm input) -> gate/up GEMM (+RMSNorm scale, SwiGLU) -> down GEMM (+residual, next-norm input)
+static int forward_bf16(llma_ctx *c, int n_seqs, int m, int t_max, bool lm_head) {
+    const llma_model_cfg &g = c->cfg;
+    const int d = g.d_model, H = g.n_heads, dh = g.head_dim, L = g.n_layers;
+    const int R = n_seqs * m;
+    hipStream_t st = c->st;
+    const int ksp_d = c->plan_qkv.KSp;          // k-steps per row tile of every activation plane that feeds a K = d GEMM
+    launch_embed_prep_bf16(c->embed, c->s.row_tok, c->n1[0], c->h, c->xhi, c->xlo, c->ssq, R, d, ksp_d, st);
+    GemmArgs base{};
+    base.rows = R; base.split = c->opt_split; base.partial = c->partial; base.ticket = c->ticket; base.eps = g.rms_eps;
+    base.ssq_tiles = d / 16; base.H = H; base.dh = dh; base.max_seq = g.max_seq; base.nx_KSp = ksp_d;
+    AttnArgs aa{};
+    aa.Qhi = c->q; aa.Qlo = c->q_lo; aa.T = c->s.T; aa.batch_slots = c->s.batch_slots; aa.n_seqs = n_seqs; aa.m = m; aa.H = H; aa.dh = dh;
+    aa.max_seq = g.max_seq; aa.n_chunks = (t_max + m + ATTN_CHUNK - 1) / ATTN_CHUNK; aa.scale = 1.0f / sqrtf((float)dh);
+    aa.po = c->po; aa.pm = c->pm; aa.pl = c->pl; aa.out_hi = c->att_hi; aa.out_lo = c->att_lo; aa.out_KSp = ksp_d;
+    for (int l = 0; l < L; ++l) {
+        GemmArgs ga = base;
+        ga.W = c->wqkv[l]; ga.plan = c->plan_qkv; ga.Xhi = c->xhi; ga.Xlo = c->xlo; ga.epi = EPI_QKV; ga.ssq_in = c->ssq;
+        ga.row_pos = c->s.row_pos; ga.row_slot = c->s.row_slot; ga.cs = c->cs_table; ga.q_hi = c->q; ga.q_lo = c->q_lo;
+        ga.k_hi = c->kc[l]; ga.k_lo = c->kc_lo[l]; ga.v_hi = c->vc[l]; ga.v_lo = c->vc_lo[l];
+        launch_gemm_bf16(ga, st);
+        aa.Khi = c->kc[l]; aa.Klo = c->kc_lo[l]; aa.Vhi = c->vc[l]; aa.Vlo = c->vc_lo[l];
+        launch_attn_bf16(aa, st);
+        ga = base;
+        ga.W = c->wo[l]; ga.plan = c->plan_o; ga.Xhi = c->att_hi; ga.Xlo = c->att_lo; ga.epi = EPI_RESID; ga.out = c->h;
+        ga.gain = c->n2[l]; ga.nx_hi = c->xhi; ga.nx_lo = c->xlo; ga.ssq_out = c->ssq;
+        launch_gemm_bf16(ga, st);
+        ga = base;
+        ga.W = c->wgu[l]; ga.plan = c->plan_gu; ga.Xhi = c->xhi; ga.Xlo = c->xlo; ga.epi = EPI_SWIGLU; ga.ssq_in = c->ssq;
+        ga.act_hi = c->act_hi; ga.act_lo = c->act_lo; ga.act_KSp = c->plan_down.KSp;
+        if (c->opt_timing && lm_head) {   // decoding steps only, not prompt processing
             EventPair ep;
             HIP_TRY(c, hipEventCreate(&ep.a));
             HIP_TRY(c, hipEventCreate(&ep.b));
             HIP_TRY(c, hipEventRecord(ep.a, st));
-            isb ? launch_gemm_bf16(ga, st) : launch_gemm_f32(ga, st);
+            launch_gemm_bf16(ga, st);
             HIP_TRY(c, hipEventRecord(ep.b, st));
             c->events.push_back(ep);
         } else {
-            isb ? launch_gemm_bf16(ga, st) : launch_gemm_f32(ga, st);
+            launch_gemm_bf16(ga, st);
         }
-        ga.W = c->wd[l]; ga.Xhi = c->act_hi; ga.Xlo = c->act_lo; ga.N = d; ga.K = F; ga.epi = EPI_RESID; ga.out = c->h;
-        ga.act_hi = ga.act_lo = nullptr;
-        isb ? launch_gemm_bf16(ga, st) : launch_gemm_f32(ga, st);
+        ga = base;
+        ga.W = c->wd[l]; ga.plan = c->plan_down; ga.Xhi = c->act_hi; ga.Xlo = c->act_lo; ga.epi = EPI_RESID; ga.out = c->h;
+        ga.gain = (l + 1 < L) ? c->n1[l + 1] : c->final_norm; ga.nx_hi = c->xhi; ga.nx_lo = c->xlo; ga.ssq_out = c->ssq;
+        launch_gemm_bf16(ga, st);
     }
     if (lm_head) {
-        launch_rmsnorm(c->h, c->final_norm, g.rms_eps, c->xhi, c->xlo, isb, R, d, st);
-        ga.W = c->lm_head; ga.Xhi = c->xhi; ga.Xlo = c->xlo; ga.N = V; ga.K = d; ga.epi = EPI_LMHEAD;
+        GemmArgs ga = base;
+        ga.W = c->lm_head; ga.plan = c->plan_lm; ga.Xhi = c->xhi; ga.Xlo = c->xlo; ga.epi = EPI_LMHEAD; ga.ssq_in = c->ssq;
         ga.out = c->logits_dump; ga.pval = c->pval; ga.pidx = c->pidx; ga.n_part = c->n_part;
-        isb ? launch_gemm_bf16(ga, st) : launch_gemm_f32(ga, st);
+        launch_gemm_bf16(ga, st);
     }
     HIP_TRY(c, hipGetLastError());
     return LLMA_OK;
+}
+
+static int forward(llma_ctx *c, int n_seqs, int m, int t_max, bool lm_head) {
+    return c->bf16 ? forward_bf16(c, n_seqs, m, t_max, lm_head) : forward_f32(c, n_seqs, m, lm_head);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -378,8 +468,9 @@ extern "C" int llma_kv_import(llma_ctx *c, int32_t seq, int32_t layer, const voi
     const size_t es = c->bf16 ? 2 : 4;
     const size_t slot_off = (size_t)seq * g.n_heads * g.max_seq * g.head_dim * es;
     void *kc = (char *)c->kc[layer] + slot_off, *vc = (char *)c->vc[layer] + slot_off;
+    void *kl = c->kv_split ? (char *)c->kc_lo[layer] + slot_off : nullptr, *vl = c->kv_split ? (char *)c->vc_lo[layer] + slot_off : nullptr;
     if (len > 0) {
-        if (c->bf16) launch_kv_import_bf16(k, v, kc, vc, g.n_heads, len, g.head_dim, g.max_seq, c->st);
+        if (c->bf16) launch_kv_import_bf16(k, v, kc, kl, vc, vl, g.n_heads, len, g.head_dim, g.max_seq, c->st);
         else launch_kv_import_f32(k, v, kc, vc, g.n_heads, len, g.head_dim, g.max_seq, c->st);
     }
     HIP_TRY(c, hipGetLastError());

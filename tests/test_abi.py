@@ -54,12 +54,12 @@ def test_argument_errors_without_device_work():
     assert lib.llma_verify_step(None, 0, null, 0, null, null, null) == llma.LLMA_E_INVAL
     assert lib.llma_destroy(None) == llma.LLMA_OK
     # llma_create rejects bad shapes before touching the device
-    cfg = llma.ModelCfgC(2, 128, 4, 31, 512, 512, 128, 1, 4, llma.LLMA_DTYPE_F32, 1e-6, 10000.0)
+    cfg = llma.ModelCfgC(2, 128, 4, 31, 512, 512, 128, 1, 4, llma.LLMA_DTYPE_F32, 0, 1e-6, 10000.0)
     w = llma.WeightsC()
     h = ctypes.c_void_p()
     assert lib.llma_create(ctypes.byref(cfg), ctypes.byref(w), None, ctypes.byref(h)) == llma.LLMA_E_INVAL
-    cfg = llma.ModelCfgC(2, 128, 4, 32, 512, 512, 128, 1, 33, llma.LLMA_DTYPE_F32, 1e-6, 10000.0)
+    cfg = llma.ModelCfgC(2, 128, 4, 32, 512, 512, 128, 1, 33, llma.LLMA_DTYPE_F32, 0, 1e-6, 10000.0)
     assert lib.llma_create(ctypes.byref(cfg), ctypes.byref(w), None, ctypes.byref(h)) == llma.LLMA_E_INVAL
-    cfg = llma.ModelCfgC(2, 128, 4, 32, 512, 512, 128, 1, 4, llma.LLMA_DTYPE_F32, 1e-6, 10000.0)
+    cfg = llma.ModelCfgC(2, 128, 4, 32, 512, 512, 128, 1, 4, llma.LLMA_DTYPE_F32, 0, 1e-6, 10000.0)
     assert lib.llma_create(ctypes.byref(cfg), ctypes.byref(w), None, ctypes.byref(h)) == llma.LLMA_E_INVAL  # null weights
     assert not h.value
