@@ -79,6 +79,9 @@ struct GemmPlan {
     int KSp;         // k-steps per feature tile incl. zero padding, = S * KSS
     int S, KSS;      // K slices and k-steps per slice
     int G;           // workgroups per slice
+    int W;           // waves per workgroup
+    int tk_ft;       // single-kernel (tile-K) variant: feature tiles per workgroup
+    int tk_waves;    //   and waves per workgroup
     int tasks;       // feature tiles (SWIGLU: gate/up tile pairs)
 };
 
@@ -91,8 +94,8 @@ struct GemmArgs {          // bf16 path (fields marked f32 are used by the fp32 
     int rows;              // valid rows
     int epi;
     int split;             // use Xlo
+    int tilek;             // 1: single-kernel tile-K variant (decoding steps), 0: slice-K + fix-up (prompt processing)
     float *partial;        // [tasks][S][tiles][NT][64] f32x4 partial sums
-    int *ticket;           // [tasks], zero between launches
     // inputs of the epilogues
     const float *ssq_in;   // [rows][ssq_tiles] sums of squares of the producer's residual rows
     int ssq_tiles;         //   rstd[row] = rsqrt(sum / (16 ssq_tiles) + eps)
@@ -111,7 +114,7 @@ struct GemmArgs {          // bf16 path (fields marked f32 are used by the fp32 
     float *pval; int *pidx; int n_part;
     // EPI_QKV: rotate, write q (tiled planes over d_model), append k, v to the cache
     const int *row_pos, *row_slot;
-    const float *cs;       // [max_seq][dh/2][2]
+    const float *row_cs;   // [rows][dh/2][2]: (cos, sin) of every row's position
     void *q_hi, *q_lo;
     void *k_hi, *k_lo, *v_hi, *v_lo;   // this layer's cache planes (lo may be null)
     int H, dh, max_seq;
@@ -122,6 +125,7 @@ struct AttnArgs {
     const void *Khi, *Klo, *Vhi, *Vlo;   // this layer's cache (lo null without kv_split); f32: Khi, Vhi
     const int *T;           // [max_batch] device lengths before the step
     const int *batch_slots; // [n_seqs]
+    int slot_const;         // >= 0: the single sequence's slot (saves a dependent load); -1: read batch_slots
     int n_seqs, m;          // rows per sequence
     int H, dh, max_seq;
     int n_chunks;           // launched chunks (upper bound over the batch)
@@ -131,4 +135,4 @@ struct AttnArgs {
     int out_KSp;
 };
 
-#define ATTN_CHUNK 256      // key positions per workgroup (4 waves x 2 groups of 32)
+#define ATTN_CHUNK 128      // key positions per workgroup (4 waves x 32)

@@ -22,6 +22,7 @@ void launch_attn_f32(const AttnArgs &a, hipStream_t st);
 // ---- shared small kernels (kernels_misc.hip)
 struct StepState {            // device pointers describing the rows of the step in flight
     int *row_tok, *row_pos, *row_slot;   // [R]
+    float *row_cs;                       // [R][head_dim/2][2] (cos, sin) of each row's position
     int *T, *pending;                    // [max_batch]
     int *batch_slots;                    // [n_seqs]
     int *keff;                           // [n_seqs] drafts actually used per sequence
@@ -38,9 +39,10 @@ struct GenState {             // device-resident state of llma_generate
 };
 
 // rows of a verify step: row (b, j) = pending[slot_b] (j = 0) or draft[b][j-1]; pos = T[slot_b] + j
-void launch_setup_step_rows(const StepState &s, int n_seqs, int m, int max_k, hipStream_t st);
-// rows of a prefill chunk for one slot: tokens prompt[off .. off+m), pos = T[slot] + j
-void launch_setup_prefill_rows(const StepState &s, const int *prompt_dev, int off, int m, int slot, hipStream_t st);
+void launch_setup_step_rows(const StepState &s, int n_seqs, int m, int max_k, const float *cs, int half, hipStream_t st);
+// rows of a prefill chunk for one slot: tokens prompt[T[slot] - *base_dev + j], pos = T[slot] + j
+void launch_setup_prefill_rows(const StepState &s, const int *prompt_dev, const int *base_dev, int m, int slot,
+                               const float *cs, int half, hipStream_t st);
 void launch_advance_T(const StepState &s, int slot, int by, hipStream_t st);
 // fp32 path: h[r][:] = embed[row_tok[r]][:]
 void launch_embed_f32(const float *embed, const int *row_tok, float *h, int R, int d, hipStream_t st);

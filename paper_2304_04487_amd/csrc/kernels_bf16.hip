@@ -12,6 +12,8 @@
 // Reduction orders are fixed by the matrix shapes and by absolute key positions, never by the
 // number of rows in the step, so row j of a k-row step is bit-identical to the same token
 // processed in a one-row step.
+#include <stdlib.h>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -132,256 +134,522 @@ void launch_embed_prep_bf16(const void *embed, const int *row_tok, const float *
 // =============================================================================================
 // skinny GEMM  Y[rows][N] = X[rows][K] . W[N][K]^T,  rows <= 16*NT
 // =============================================================================================
-// The K axis is cut into S slices.  A workgroup belongs to one slice: it copies that slice of
-// the activations (hi and lo planes, already in B-operand order) into LDS once, then each of its
-// 4 waves walks over feature tiles, streaming the slice's KSS weight blocks of a tile straight
-// from HBM into MFMA A operands (non-temporal, 1 KiB per wave-load) and taking B operands from
-// LDS.  D[i][n] = sum_k A[i][k] B[k][n] with i = feature, n = activation row, so lane l ends
-// with features 4(l/16)..+3 of row l%16.  Each (tile, slice) partial goes to a scratch buffer;
-// the wave that draws the last ticket of a tile adds the S partials in slice order (so the sum
-// does not depend on arrival order) and runs the fused epilogue.  S, KSS and the tile walk
-// depend on the matrix shape only.
-template <int NT, int EPI, bool SPLIT>
-__global__ __launch_bounds__(256) void gemm_slicek_bf16(GemmArgs a) {
-    constexpr int TILES = (EPI == EPI_SWIGLU) ? 2 : 1;
-    constexpr int U = (TILES == 2) ? 4 : 8;
-    constexpr int PL = SPLIT ? 2 : 1;
-    extern __shared__ u32x4 xs[];                  // [PL][NT][KSS][64], then rstd[16*NT] floats
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const GemmPlan &p = a.plan;
-    const int S = p.S, KSS = p.KSS, KSp = p.KSp;
-    const int s = blockIdx.x % S, g = blockIdx.x / S;
-    const int ks0 = s * KSS;
-    float *rstd_s = (float *)(xs + (size_t)PL * NT * KSS * 64);
+// Two kernels.  The first streams the weights: the K axis is cut into S slices, a workgroup
+// belongs to one slice, copies that slice of the activations (hi and lo planes, already in
+// B-operand order) into LDS once, then each of its waves walks over feature tiles, streaming the
+// slice's KSS weight blocks of a tile straight from HBM into MFMA A operands (non-temporal,
+// 1 KiB per wave-load, next batch in flight while the current one is multiplied) and taking B
+// operands from LDS.  D[i][n] = sum_k A[i][k] B[k][n] with i = feature, n = activation row, so
+// lane l ends with features 4(l/16)..+3 of row l%16.  Each (tile, slice) partial goes to a
+// scratch buffer.  The second kernel adds the S partials of every tile in slice order and runs
+// the fused epilogue.  S, KSS and the tile walk depend on the matrix shape only.
+// ---- fused epilogues.  Lane l holds features 16 task + 4 (l/16) .. +3 of row 16 t + l%16.
+// Everything an epilogue reads from memory is fetched by epi_prefetch() before the partial sums
+// are reduced, so the kernel has one memory round trip on its critical path instead of three.
+template <int NT>
+struct EpiIn {
+    f32x4 hv[NT], gv;          // RESID: residual values, next norm's gains
+    int pos[NT], slot[NT];     // QKV: position and cache slot of the row
+    f32x4 cs01[NT], cs23[NT];  // QKV: (cos, sin) of the lane's four rotary pairs
+};
 
-    // ---- activations of this slice -> LDS
-    {
-        const int per_plane = NT * KSS * 64;       // 16-byte pieces
-        for (int i = threadIdx.x; i < per_plane; i += 256) {
-            const int t = i / (KSS * 64), rem = i % (KSS * 64);
-            const size_t src = ((size_t)t * KSp + ks0) * 64 + rem;
-            xs[i] = ((const u32x4 *)a.Xhi)[src];
-            if (SPLIT) xs[per_plane + i] = ((const u32x4 *)a.Xlo)[src];
+template <int NT, int EPI>
+__device__ __forceinline__ void epi_prefetch(const GemmArgs &a, const GemmPlan &p, int task, int lane, EpiIn<NT> &in) {
+    const int n = lane & 15, g4 = lane >> 4;
+    const int f0 = task * 16 + g4 * 4;
+    if (EPI == EPI_RESID) in.gv = *(const f32x4 *)(a.gain + f0);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const int row = t * 16 + n;
+        const bool live = row < a.rows;
+        if (EPI == EPI_RESID) {
+            in.hv[t] = live ? *(const f32x4 *)(a.out + (size_t)row * p.N + f0) : (f32x4){0.f, 0.f, 0.f, 0.f};
+        } else if (EPI == EPI_QKV) {
+            in.pos[t] = live ? a.row_pos[row] : 0;
+            in.slot[t] = live ? a.row_slot[row] : 0;
+            const int tps = a.H * a.dh / 16, tph = a.dh / 16, half = a.dh / 2;
+            const int j = (task % tps) % tph;
+            const int i0 = 8 * j + (g4 & 1) * 4;
+            const f32x4 *cp = (const f32x4 *)(a.row_cs + ((size_t)(live ? row : 0) * half + i0) * 2);
+            in.cs01[t] = cp[0];
+            in.cs23[t] = cp[1];
         }
     }
-    // ---- rstd of the rows from the producer's per-tile sums of squares: thread (row, i) adds
-    //      tiles i, i+16, ... then the 16 threads of a row are combined by butterfly
-    if (EPI != EPI_RESID) {
-        const int row = threadIdx.x >> 4, i = threadIdx.x & 15;
+}
+
+template <int NT, int EPI, int TILES>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, const GemmPlan &p, int task, int lane,
+                                              f32x4 (&acc)[TILES][NT], const float *rstd_s, const EpiIn<NT> &in) {
+    const int n = lane & 15, g4 = lane >> 4;
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            const int r = t * 16 + row;
+    for (int t = 0; t < NT; ++t) {
+        const int row = t * 16 + n;
+        const bool live = row < a.rows;
+        const int f0 = task * 16 + g4 * 4;
+        if (EPI == EPI_RESID) {
+            float x[4];
             float ss = 0.f;
-            if (r < a.rows)
-                for (int j = i; j < a.ssq_tiles; j += 16) ss += a.ssq_in[(size_t)r * a.ssq_tiles + j];
+            const f32x4 hv = in.hv[t] + acc[0][t];
 #pragma unroll
-            for (int off = 1; off < 16; off <<= 1) ss += __shfl_xor(ss, off);
-            if (i == 0) rstd_s[r] = 1.0f / sqrtf(ss / (float)(a.ssq_tiles * 16) + a.eps);
-        }
-    }
-    __syncthreads();
-
-    const int stride = p.G * 4;
-    for (int task = g * 4 + wave; task < p.tasks; task += stride) {
-        const u32x4 *wp[TILES];
-        wp[0] = (const u32x4 *)a.W + ((size_t)task * KSp + ks0) * 64 + lane;
-        if (TILES == 2) wp[1] = (const u32x4 *)a.W + ((size_t)(task + p.tasks) * KSp + ks0) * 64 + lane;
-        f32x4 acc[TILES][NT];
-#pragma unroll
-        for (int i = 0; i < TILES; ++i)
-#pragma unroll
-            for (int t = 0; t < NT; ++t) acc[i][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
-        int k = 0;
-        for (; k + U <= KSS; k += U) {
-            u32x4 av[TILES][U];
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int i = 0; i < TILES; ++i) av[i][u] = __builtin_nontemporal_load(wp[i] + (k + u) * 64);
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int t = 0; t < NT; ++t) {
-                    const u32x4 bh = xs[(t * KSS + k + u) * 64 + lane];
-#pragma unroll
-                    for (int i = 0; i < TILES; ++i) acc[i][t] = mfma16x16x32(av[i][u], bh, acc[i][t]);
-                    if (SPLIT) {
-                        const u32x4 bl = xs[((NT + t) * KSS + k + u) * 64 + lane];
-#pragma unroll
-                        for (int i = 0; i < TILES; ++i) acc[i][t] = mfma16x16x32(av[i][u], bl, acc[i][t]);
-                    }
-                }
-        }
-        for (; k < KSS; ++k) {
-            u32x4 av[TILES];
-#pragma unroll
-            for (int i = 0; i < TILES; ++i) av[i] = __builtin_nontemporal_load(wp[i] + k * 64);
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const u32x4 bh = xs[(t * KSS + k) * 64 + lane];
-#pragma unroll
-                for (int i = 0; i < TILES; ++i) acc[i][t] = mfma16x16x32(av[i], bh, acc[i][t]);
-                if (SPLIT) {
-                    const u32x4 bl = xs[((NT + t) * KSS + k) * 64 + lane];
-#pragma unroll
-                    for (int i = 0; i < TILES; ++i) acc[i][t] = mfma16x16x32(av[i], bl, acc[i][t]);
-                }
+            for (int r = 0; r < 4; ++r) { ss += hv[r] * hv[r]; x[r] = hv[r] * in.gv[r]; }
+            if (live) {
+                *(f32x4 *)(a.out + (size_t)row * p.N + f0) = hv;
+                u32x2 hi, lo;
+                split4(x, hi, lo);
+                const size_t o = xtile_off(row, f0, a.nx_KSp);
+                *(u32x2 *)((bf16_t *)a.nx_hi + o) = hi;
+                *(u32x2 *)((bf16_t *)a.nx_lo + o) = lo;
             }
-        }
-
-        // ---- (tile, slice) partial -> scratch; last ticket of the tile adds them in slice order
-        if (S > 1) {
-            f32x4 *pp = (f32x4 *)a.partial + ((size_t)task * S + s) * (TILES * NT * 64) + lane;
+            ss += __shfl_xor(ss, 16);
+            ss += __shfl_xor(ss, 32);
+            if (live && g4 == 0) a.ssq_out[(size_t)row * (p.N / 16) + task] = ss;
+        } else if (EPI == EPI_SWIGLU) {
+            if (live) {
+                const float rs = rstd_s[row];
+                float v[4];
 #pragma unroll
-            for (int i = 0; i < TILES; ++i)
-#pragma unroll
-                for (int t = 0; t < NT; ++t) pp[(i * NT + t) * 64] = acc[i][t];
-            __threadfence();
-            int tk = 0;
-            if (lane == 0) tk = atomicAdd(a.ticket + task, 1);
-            tk = __shfl(tk, 0);
-            if (tk != S - 1) continue;
-            __threadfence();
-            const f32x4 *pq = (const f32x4 *)a.partial + (size_t)task * S * (TILES * NT * 64) + lane;
-#pragma unroll
-            for (int i = 0; i < TILES; ++i)
-#pragma unroll
-                for (int t = 0; t < NT; ++t) {
-                    f32x4 sum = pq[(i * NT + t) * 64];
-                    for (int s2 = 1; s2 < S; ++s2) sum += pq[((size_t)s2 * TILES * NT + i * NT + t) * 64];
-                    acc[i][t] = sum;
+                for (int r = 0; r < 4; ++r) {
+                    const float gg = acc[0][t][r] * rs, uu = acc[1][t][r] * rs;
+                    v[r] = gg / (1.0f + __expf(-gg)) * uu;
                 }
-            if (lane == 0) a.ticket[task] = 0;
-        }
-
-        // ---- epilogue: lane holds features 16 task + 4 g4 .. +3 of row 16 t + n
-        const int n = lane & 15, g4 = lane >> 4;
+                u32x2 hi, lo;
+                split4(v, hi, lo);
+                const size_t o = xtile_off(row, f0, a.act_KSp);
+                *(u32x2 *)((bf16_t *)a.act_hi + o) = hi;
+                *(u32x2 *)((bf16_t *)a.act_lo + o) = lo;
+            }
+        } else if (EPI == EPI_LMHEAD) {
+            const float rs = live ? rstd_s[row] : 0.f;
+            const f32x4 lg = acc[0][t] * rs;
+            if (a.out != nullptr && live) *(f32x4 *)(a.out + (size_t)row * p.N + f0) = lg;
+            float bv = lg[0];
+            int bi = f0;
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            const int row = t * 16 + n;
-            const bool live = row < a.rows;
-            const int f0 = task * 16 + g4 * 4;
-            if (EPI == EPI_RESID) {
-                float hn[4], x[4];
-                float ss = 0.f;
+            for (int r = 1; r < 4; ++r)
+                if (lg[r] > bv) { bv = lg[r]; bi = f0 + r; }
+#pragma unroll
+            for (int sh = 16; sh <= 32; sh <<= 1) {
+                const float ov = __shfl_xor(bv, sh);
+                const int oi = __shfl_xor(bi, sh);
+                if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+            }
+            if (g4 == 0 && live) {
+                a.pval[(size_t)row * a.n_part + task] = bv;
+                a.pidx[(size_t)row * a.n_part + task] = bi;
+            }
+        } else if (EPI == EPI_QKV) {
+            // tile rows 0..7 = rotary first halves i, rows 8..15 = their partners i + dh/2
+            const int d = a.H * a.dh, tps = d / 16, tph = a.dh / 16;
+            const int sec = task / tps, tin = task % tps;
+            const int head = tin / tph, j = tin % tph;
+            const float rs = live ? rstd_s[row] : 0.f;
+            float v[4], o4[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[r] = acc[0][t][r] * rs;
+            const int pos = in.pos[t];
+            const size_t head_base = ((size_t)in.slot[t] * a.H + head) * (size_t)a.max_seq * a.dh;
+            if (sec < 2) {
+                const int half = a.dh / 2;
+                const int i0 = 8 * j + (g4 & 1) * 4;
+                const float cs[8] = {in.cs01[t][0], in.cs01[t][1], in.cs01[t][2], in.cs01[t][3],
+                                     in.cs23[t][0], in.cs23[t][1], in.cs23[t][2], in.cs23[t][3]};
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float pr = __shfl_xor(v[r], 32);
+                    o4[r] = (g4 < 2) ? (v[r] * cs[2 * r] - pr * cs[2 * r + 1]) : (v[r] * cs[2 * r] + pr * cs[2 * r + 1]);
+                }
+                const int c0 = (g4 < 2) ? i0 : half + i0;
                 if (live) {
-                    f32x4 *hp = (f32x4 *)(a.out + (size_t)row * p.N + f0);
-                    const f32x4 hv = *hp + acc[0][t];
-                    *hp = hv;
-                    const f32x4 gv = *(const f32x4 *)(a.gain + f0);
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) { hn[r] = hv[r]; ss += hn[r] * hn[r]; x[r] = hn[r] * gv[r]; }
                     u32x2 hi, lo;
-                    split4(x, hi, lo);
-                    const size_t o = xtile_off(row, f0, a.nx_KSp);
-                    *(u32x2 *)((bf16_t *)a.nx_hi + o) = hi;
-                    *(u32x2 *)((bf16_t *)a.nx_lo + o) = lo;
-                }
-                ss += __shfl_xor(ss, 16);
-                ss += __shfl_xor(ss, 32);
-                if (live && g4 == 0) a.ssq_out[(size_t)row * (p.N / 16) + task] = ss;
-            } else if (EPI == EPI_SWIGLU) {
-                if (live) {
-                    const float rs = rstd_s[row];
-                    float v[4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const float gg = acc[0][t][r] * rs, uu = acc[1][t][r] * rs;
-                        v[r] = gg / (1.0f + __expf(-gg)) * uu;
+                    split4(o4, hi, lo);
+                    if (sec == 0) {
+                        const size_t o = xtile_off(row, head * a.dh + c0, d / 32);
+                        *(u32x2 *)((bf16_t *)a.q_hi + o) = hi;
+                        *(u32x2 *)((bf16_t *)a.q_lo + o) = lo;
+                    } else {
+                        const size_t o = head_base + kcache_off(pos, c0, a.dh);
+                        *(u32x2 *)((bf16_t *)a.k_hi + o) = hi;
+                        if (a.k_lo) *(u32x2 *)((bf16_t *)a.k_lo + o) = lo;
                     }
-                    u32x2 hi, lo;
-                    split4(v, hi, lo);
-                    const size_t o = xtile_off(row, f0, a.act_KSp);
-                    *(u32x2 *)((bf16_t *)a.act_hi + o) = hi;
-                    *(u32x2 *)((bf16_t *)a.act_lo + o) = lo;
                 }
-            } else if (EPI == EPI_LMHEAD) {
-                const float rs = live ? rstd_s[row] : 0.f;
-                const f32x4 lg = acc[0][t] * rs;
-                if (a.out != nullptr && live) *(f32x4 *)(a.out + (size_t)row * p.N + f0) = lg;
-                float bv = lg[0];
-                int bi = f0;
+            } else if (live) {
+                const int c0 = j * 16 + g4 * 4;
 #pragma unroll
-                for (int r = 1; r < 4; ++r)
-                    if (lg[r] > bv) { bv = lg[r]; bi = f0 + r; }
-#pragma unroll
-                for (int sh = 16; sh <= 32; sh <<= 1) {
-                    const float ov = __shfl_xor(bv, sh);
-                    const int oi = __shfl_xor(bi, sh);
-                    if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-                }
-                if (g4 == 0 && live) {
-                    a.pval[(size_t)row * a.n_part + task] = bv;
-                    a.pidx[(size_t)row * a.n_part + task] = bi;
-                }
-            } else if (EPI == EPI_QKV) {
-                // tile rows 0..7 = rotary first halves i, rows 8..15 = their partners i + dh/2
-                const int d = a.H * a.dh, tps = d / 16, tph = a.dh / 16;
-                const int sec = task / tps, tin = task % tps;
-                const int head = tin / tph, j = tin % tph;
-                const float rs = live ? rstd_s[row] : 0.f;
-                float v[4], o4[4];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) v[r] = acc[0][t][r] * rs;
-                const int pos = live ? a.row_pos[row] : 0;
-                const int slot = live ? a.row_slot[row] : 0;
-                const size_t head_base = ((size_t)slot * a.H + head) * (size_t)a.max_seq * a.dh;
-                if (sec < 2) {
-                    const int half = a.dh / 2;
-                    const int i0 = 8 * j + (g4 & 1) * 4;
-                    float pr[4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) pr[r] = __shfl_xor(v[r], 32);
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const float c = a.cs[((size_t)pos * half + i0 + r) * 2], sn = a.cs[((size_t)pos * half + i0 + r) * 2 + 1];
-                        o4[r] = (g4 < 2) ? (v[r] * c - pr[r] * sn) : (v[r] * c + pr[r] * sn);
-                    }
-                    const int c0 = (g4 < 2) ? i0 : half + i0;
-                    if (live) {
-                        u32x2 hi, lo;
-                        split4(o4, hi, lo);
-                        if (sec == 0) {
-                            const size_t o = xtile_off(row, head * a.dh + c0, d / 32);
-                            *(u32x2 *)((bf16_t *)a.q_hi + o) = hi;
-                            *(u32x2 *)((bf16_t *)a.q_lo + o) = lo;
-                        } else {
-                            const size_t o = head_base + kcache_off(pos, c0, a.dh);
-                            *(u32x2 *)((bf16_t *)a.k_hi + o) = hi;
-                            if (a.k_lo) *(u32x2 *)((bf16_t *)a.k_lo + o) = lo;
-                        }
-                    }
-                } else if (live) {
-                    const int c0 = j * 16 + g4 * 4;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        bf16_t hi, lo;
-                        split_bf16(v[r], hi, lo);
-                        const size_t o = head_base + vcache_off(pos, c0 + r, a.dh);
-                        ((bf16_t *)a.v_hi)[o] = hi;
-                        if (a.v_lo) ((bf16_t *)a.v_lo)[o] = lo;
-                    }
+                for (int r = 0; r < 4; ++r) {
+                    bf16_t hi, lo;
+                    split_bf16(v[r], hi, lo);
+                    const size_t o = head_base + vcache_off(pos, c0 + r, a.dh);
+                    ((bf16_t *)a.v_hi)[o] = hi;
+                    if (a.v_lo) ((bf16_t *)a.v_lo)[o] = lo;
                 }
             }
         }
     }
 }
 
-template <int NT, int EPI>
-static void launch_gemm_nt_epi(const GemmArgs &a, hipStream_t st) {
+template <int NT, int TILES, bool SPLIT>
+__global__ __launch_bounds__(512) void gemm_slicek_bf16(GemmArgs a) {
+    constexpr int UH = 8 / TILES;                  // k-steps per load batch: 8 KiB in flight per wave and batch
+    constexpr int PL = SPLIT ? 2 : 1;
+    extern __shared__ u32x4 xs[];                  // [PL][NT][KSS][64]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, W = blockDim.x >> 6;
     const GemmPlan &p = a.plan;
-    const int planes = a.split ? 2 : 1;
-    const size_t lds = (size_t)planes * NT * p.KSS * 1024 + 64 * sizeof(float);
-    dim3 grid(p.S * p.G), block(256);
+    const int S = p.S, KSS = p.KSS, KSp = p.KSp;
+    const int s = blockIdx.x % S, g = blockIdx.x / S;
+    const int ks0 = s * KSS;
+    const int NB = (KSS + UH - 1) / UH;            // load batches per (tile, slice)
+    const int stride = p.G * W;
+
+    // one batch of weight blocks of (task, batch kb): TILES x UH coalesced 1 KiB wave-loads.  A ragged
+    // last batch re-reads the slice's last block instead of running past it.
+    auto issue = [&](int task, int kb, u32x4 (&buf)[TILES][UH]) {
+#pragma unroll
+        for (int i = 0; i < TILES; ++i) {
+            const u32x4 *wp = (const u32x4 *)a.W + ((size_t)(task + i * p.tasks) * KSp + ks0) * 64 + lane;
+#pragma unroll
+            for (int u = 0; u < UH; ++u) {
+                int k = kb * UH + u;
+                k = k < KSS ? k : KSS - 1;
+                buf[i][u] = __builtin_nontemporal_load(wp + k * 64);
+            }
+        }
+    };
+    auto compute = [&](int kb, u32x4 (&buf)[TILES][UH], f32x4 (&acc)[TILES][NT]) {
+#pragma unroll
+        for (int u = 0; u < UH; ++u) {
+            const int k = kb * UH + u;
+            if (k < KSS) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    const u32x4 bh = xs[(t * KSS + k) * 64 + lane];
+#pragma unroll
+                    for (int i = 0; i < TILES; ++i) acc[i][t] = mfma16x16x32(buf[i][u], bh, acc[i][t]);
+                    if (SPLIT) {
+                        const u32x4 bl = xs[((NT + t) * KSS + k) * 64 + lane];
+#pragma unroll
+                        for (int i = 0; i < TILES; ++i) acc[i][t] = mfma16x16x32(buf[i][u], bl, acc[i][t]);
+                    }
+                }
+            }
+        }
+    };
+    // the (tile, slice) partial of this wave: one coalesced 1 KiB store per accumulator
+    auto store_partial = [&](int task, f32x4 (&acc)[TILES][NT]) {
+        f32x4 *pp = (f32x4 *)a.partial + ((size_t)task * S + s) * (TILES * NT * 64) + lane;
+#pragma unroll
+        for (int i = 0; i < TILES; ++i)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) pp[(i * NT + t) * 64] = acc[i][t];
+    };
+
+    int task = g * W + wave, kb = 0;
+    u32x4 bufA[TILES][UH], bufB[TILES][UH];
+    if (task < p.tasks) issue(task, 0, bufA);      // weights do not depend on the activations: start streaming first
+
+    // ---- activations of this slice -> LDS (all loads of a thread in flight together)
+    {
+        const int per_plane = NT * KSS * 64;       // 16-byte pieces per plane
+        for (int base = 0; base < per_plane; base += 4 * blockDim.x) {
+            u32x4 vh[4], vl[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int i = base + j * blockDim.x + threadIdx.x;
+                if (i < per_plane) {
+                    const int t = i / (KSS * 64), rem = i % (KSS * 64);
+                    const size_t src = ((size_t)t * KSp + ks0) * 64 + rem;
+                    vh[j] = ((const u32x4 *)a.Xhi)[src];
+                    if (SPLIT) vl[j] = ((const u32x4 *)a.Xlo)[src];
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int i = base + j * blockDim.x + threadIdx.x;
+                if (i < per_plane) {
+                    xs[i] = vh[j];
+                    if (SPLIT) xs[per_plane + i] = vl[j];
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- software pipeline over the wave's (tile, batch) sequence: while one batch feeds the
+    //      MFMAs the next one (of this tile or of the wave's next tile) is already in flight
+    f32x4 acc[TILES][NT];
+    while (task < p.tasks) {
+        {   // compute bufA, prefetch into bufB
+            int ntask = task, nkb = kb + 1;
+            if (nkb == NB) { nkb = 0; ntask = task + stride; }
+            if (ntask < p.tasks) issue(ntask, nkb, bufB);
+            if (kb == 0) {
+#pragma unroll
+                for (int i = 0; i < TILES; ++i)
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) acc[i][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            }
+            compute(kb, bufA, acc);
+            if (kb == NB - 1) store_partial(task, acc);
+            task = ntask; kb = nkb;
+        }
+        if (task >= p.tasks) break;
+        {   // compute bufB, prefetch into bufA
+            int ntask = task, nkb = kb + 1;
+            if (nkb == NB) { nkb = 0; ntask = task + stride; }
+            if (ntask < p.tasks) issue(ntask, nkb, bufA);
+            if (kb == 0) {
+#pragma unroll
+                for (int i = 0; i < TILES; ++i)
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) acc[i][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            }
+            compute(kb, bufB, acc);
+            if (kb == NB - 1) store_partial(task, acc);
+            task = ntask; kb = nkb;
+        }
+    }
+}
+
+// Second half of the GEMM: one wave per feature tile adds the tile's S slice partials in slice
+// order (a fixed order, so the sum does not depend on which workgroup finished first) and runs
+// the fused epilogue.  The kernel boundary between the two halves is the only synchronisation.
+template <int NT, int EPI>
+__global__ __launch_bounds__(256) void gemm_fixup_bf16(GemmArgs a) {
+    constexpr int TILES = (EPI == EPI_SWIGLU) ? 2 : 1;
+    __shared__ float rstd_s[16 * NT];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const GemmPlan &p = a.plan;
+    const int S = p.S;
+    const int task = blockIdx.x * 4 + wave;
+    f32x4 acc[TILES][NT];
+    EpiIn<NT> in;
+    if (task < p.tasks) epi_prefetch<NT, EPI>(a, p, task, lane, in);
+    if (task < p.tasks) {                          // partial loads first, the rstd reduction overlaps them
+        const f32x4 *pq = (const f32x4 *)a.partial + (size_t)task * S * (TILES * NT * 64) + lane;
+#pragma unroll
+        for (int i = 0; i < TILES; ++i)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const f32x4 *q = pq + (i * NT + t) * 64;
+                f32x4 sum = (f32x4){0.f, 0.f, 0.f, 0.f};
+                for (int s0 = 0; s0 < S; s0 += 8) {                  // 8 independent loads in flight, added in slice order
+                    f32x4 v[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (s0 + j < S) v[j] = q[(size_t)(s0 + j) * (TILES * NT * 64)];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (s0 + j < S) sum = (s0 + j == 0) ? v[j] : sum + v[j];
+                }
+                acc[i][t] = sum;
+            }
+    }
+    // rstd of the rows from the producer's per-tile sums of squares: the 16 threads of a row each
+    // add one contiguous chunk of tiles in order, then combine by butterfly
+    if (EPI != EPI_RESID) {
+        const int row = threadIdx.x >> 4, i = threadIdx.x & 15;
+        const int chunk = (a.ssq_tiles + 15) / 16;
+        const int j0 = i * chunk, j1 = (j0 + chunk < a.ssq_tiles) ? j0 + chunk : a.ssq_tiles;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int r = t * 16 + row;
+            float ss = 0.f;
+            if (r < a.rows) {
+                const float *sp = a.ssq_in + (size_t)r * a.ssq_tiles;
+                for (int j = j0; j < j1; j += 16) {                      // 16 loads in flight, added in tile order
+                    float v[16];
+#pragma unroll
+                    for (int u = 0; u < 16; ++u)
+                        if (j + u < j1) v[u] = sp[j + u];
+#pragma unroll
+                    for (int u = 0; u < 16; ++u)
+                        if (j + u < j1) ss += v[u];
+                }
+            }
+#pragma unroll
+            for (int off = 1; off < 16; off <<= 1) ss += __shfl_xor(ss, off);
+            if (i == 0) rstd_s[r] = 1.0f / sqrtf(ss / (float)(a.ssq_tiles * 16) + a.eps);
+        }
+        __syncthreads();
+    }
+    if (task < p.tasks) gemm_epilogue<NT, EPI, TILES>(a, p, task, lane, acc, rstd_s, in);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Single-kernel variant ("tile-K"): one workgroup per FT consecutive feature tiles, its waves
+// split the K axis, B operands come straight from the tiled activation planes (1 KiB contiguous
+// per k-step and plane, shared through L2 by all workgroups), partial sums meet in LDS in wave
+// order and the first FT waves run the fused epilogue.  No scratch traffic and no second
+// kernel; more operand traffic per weight byte than the slice-K kernel.
+// ---------------------------------------------------------------------------------------------
+template <int NT, int EPI, bool SPLIT, int FT>
+__global__ __launch_bounds__(1024) void gemm_tilek_bf16(GemmArgs a) {
+    constexpr int TILES = (EPI == EPI_SWIGLU) ? 2 : 1;
+    constexpr int AT = FT * TILES;                 // weight tiles per k-step
+    constexpr int UB = (AT * NT >= 4) ? 1 : 2;     // k-steps per load batch
+    constexpr int PL = SPLIT ? 2 : 1;
+    extern __shared__ f32x4 red[];                 // [W][AT][NT][64], then rstd[16*NT] floats
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, W = blockDim.x >> 6;
+    const GemmPlan &p = a.plan;
+    const int KSp = p.KSp;
+    const int task0 = blockIdx.x * FT;
+    const int ks0 = (int)(((long)KSp * wave) / W), ks1 = (int)(((long)KSp * (wave + 1)) / W);
+    float *rstd_s = (float *)(red + (size_t)W * AT * NT * 64);
+
+    const u32x4 *wp[AT];
+#pragma unroll
+    for (int f = 0; f < FT; ++f)
+#pragma unroll
+        for (int i = 0; i < TILES; ++i) {
+            int task = task0 + f;
+            task = task < p.tasks ? task : p.tasks - 1;          // ragged last workgroup: recompute the last tile
+            wp[f * TILES + i] = (const u32x4 *)a.W + ((size_t)(task + i * p.tasks) * KSp) * 64 + lane;
+        }
+    const u32x4 *xh = (const u32x4 *)a.Xhi + lane, *xl = (const u32x4 *)a.Xlo + lane;
+
+    auto issue = [&](int ks, u32x4 (&av)[AT][UB], u32x4 (&bv)[PL][NT][UB]) {
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+            int k = ks + u;
+            k = k < ks1 ? k : ks1 - 1;
+#pragma unroll
+            for (int i = 0; i < AT; ++i) av[i][u] = __builtin_nontemporal_load(wp[i] + (size_t)k * 64);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                bv[0][t][u] = xh[((size_t)t * KSp + k) * 64];
+                if (SPLIT) bv[PL - 1][t][u] = xl[((size_t)t * KSp + k) * 64];
+            }
+        }
+    };
+    f32x4 acc[AT][NT];
+#pragma unroll
+    for (int i = 0; i < AT; ++i)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[i][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    auto compute = [&](int ks, u32x4 (&av)[AT][UB], u32x4 (&bv)[PL][NT][UB]) {
+#pragma unroll
+        for (int u = 0; u < UB; ++u)
+            if (ks + u < ks1) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+#pragma unroll
+                    for (int i = 0; i < AT; ++i) {
+                        acc[i][t] = mfma16x16x32(av[i][u], bv[0][t][u], acc[i][t]);
+                        if (SPLIT) acc[i][t] = mfma16x16x32(av[i][u], bv[PL - 1][t][u], acc[i][t]);
+                    }
+            }
+    };
+
+    u32x4 avA[AT][UB], bvA[PL][NT][UB], avB[AT][UB], bvB[PL][NT][UB];
+    int ks = ks0;
+    if (ks < ks1) issue(ks, avA, bvA);
+    // epilogue inputs and rstd while the first batch is in flight
+    EpiIn<NT> in;
+    const int my_task = task0 + wave;                           // waves 0..FT-1 finish one tile each
+    const bool finisher = wave < FT && my_task < p.tasks;
+    if (finisher) epi_prefetch<NT, EPI>(a, p, my_task, lane, in);
+    if (EPI != EPI_RESID && threadIdx.x < 256) {
+        const int row = threadIdx.x >> 4, i = threadIdx.x & 15;
+        const int chunk = (a.ssq_tiles + 15) / 16;
+        const int j0 = i * chunk, j1 = (j0 + chunk < a.ssq_tiles) ? j0 + chunk : a.ssq_tiles;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int r = t * 16 + row;
+            float ss = 0.f;
+            if (r < a.rows) {
+                const float *sp = a.ssq_in + (size_t)r * a.ssq_tiles;
+                for (int j = j0; j < j1; j += 16) {
+                    float v[16];
+#pragma unroll
+                    for (int u = 0; u < 16; ++u)
+                        if (j + u < j1) v[u] = sp[j + u];
+#pragma unroll
+                    for (int u = 0; u < 16; ++u)
+                        if (j + u < j1) ss += v[u];
+                }
+            }
+#pragma unroll
+            for (int off = 1; off < 16; off <<= 1) ss += __shfl_xor(ss, off);
+            if (i == 0) rstd_s[r] = 1.0f / sqrtf(ss / (float)(a.ssq_tiles * 16) + a.eps);
+        }
+    }
+    while (ks < ks1) {
+        if (ks + UB < ks1) issue(ks + UB, avB, bvB);
+        compute(ks, avA, bvA);
+        ks += UB;
+        if (ks >= ks1) break;
+        if (ks + UB < ks1) issue(ks + UB, avA, bvA);
+        compute(ks, avB, bvB);
+        ks += UB;
+    }
+    // ---- the waves' partial sums meet in LDS and are added in wave order
+#pragma unroll
+    for (int i = 0; i < AT; ++i)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) red[((wave * AT + i) * NT + t) * 64 + lane] = acc[i][t];
+    __syncthreads();
+    if (!finisher) return;
+    f32x4 sum[TILES][NT];
+#pragma unroll
+    for (int i = 0; i < TILES; ++i)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            f32x4 v = red[((0 * AT + wave * TILES + i) * NT + t) * 64 + lane];
+            for (int w = 1; w < W; ++w) v += red[((w * AT + wave * TILES + i) * NT + t) * 64 + lane];
+            sum[i][t] = v;
+        }
+    gemm_epilogue<NT, EPI, TILES>(a, p, my_task, lane, sum, rstd_s, in);
+}
+
+template <int NT, int EPI, int FT>
+static void launch_tilek(const GemmArgs &a, hipStream_t st) {
+    constexpr int TILES = (EPI == EPI_SWIGLU) ? 2 : 1;
+    const GemmPlan &p = a.plan;
+    const int W = p.tk_waves;
+    const size_t lds = (size_t)W * FT * TILES * NT * 1024 + 256;
+    dim3 grid((p.tasks + FT - 1) / FT), block(W * 64);
     if (a.split) {
         static bool attr_done = false;
-        if (!attr_done) { (void)hipFuncSetAttribute((const void *)gemm_slicek_bf16<NT, EPI, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); attr_done = true; }
-        hipLaunchKernelGGL((gemm_slicek_bf16<NT, EPI, true>), grid, block, lds, st, a);
+        if (!attr_done) { (void)hipFuncSetAttribute((const void *)gemm_tilek_bf16<NT, EPI, true, FT>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); attr_done = true; }
+        hipLaunchKernelGGL((gemm_tilek_bf16<NT, EPI, true, FT>), grid, block, lds, st, a);
     } else {
         static bool attr_done = false;
-        if (!attr_done) { (void)hipFuncSetAttribute((const void *)gemm_slicek_bf16<NT, EPI, false>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); attr_done = true; }
-        hipLaunchKernelGGL((gemm_slicek_bf16<NT, EPI, false>), grid, block, lds, st, a);
+        if (!attr_done) { (void)hipFuncSetAttribute((const void *)gemm_tilek_bf16<NT, EPI, false, FT>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); attr_done = true; }
+        hipLaunchKernelGGL((gemm_tilek_bf16<NT, EPI, false, FT>), grid, block, lds, st, a);
     }
+}
+
+template <int NT, int EPI>
+static void launch_gemm_nt_epi(const GemmArgs &a, hipStream_t st) {
+    constexpr int TILES = (EPI == EPI_SWIGLU) ? 2 : 1;
+    const GemmPlan &p = a.plan;
+    if (a.tilek) {                                  // single-kernel variant (decoding steps)
+        if (TILES == 2) {
+            if (p.tk_ft == 1) launch_tilek<NT, EPI, 1>(a, st);
+            else if (p.tk_ft == 2) launch_tilek<NT, EPI, 2>(a, st);
+            else launch_tilek<NT, EPI, 3>(a, st);
+        } else {
+            if (p.tk_ft == 1) launch_tilek<NT, EPI, 1>(a, st);
+            else if (p.tk_ft == 2) launch_tilek<NT, EPI, 2>(a, st);
+            else if (p.tk_ft == 3) launch_tilek<NT, EPI, 3>(a, st);
+            else if (p.tk_ft == 4) launch_tilek<NT, EPI, 4>(a, st);
+            else if (p.tk_ft <= 6) launch_tilek<NT, EPI, 6>(a, st);
+            else launch_tilek<NT, EPI, 8>(a, st);
+        }
+        return;
+    }
+    const int planes = a.split ? 2 : 1;
+    const size_t lds = (size_t)planes * NT * p.KSS * 1024;
+    dim3 grid(p.S * p.G), block(p.W * 64);
+    if (a.split) {
+        static bool attr_done = false;
+        if (!attr_done) { (void)hipFuncSetAttribute((const void *)gemm_slicek_bf16<NT, TILES, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); attr_done = true; }
+        hipLaunchKernelGGL((gemm_slicek_bf16<NT, TILES, true>), grid, block, lds, st, a);
+    } else {
+        static bool attr_done = false;
+        if (!attr_done) { (void)hipFuncSetAttribute((const void *)gemm_slicek_bf16<NT, TILES, false>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); attr_done = true; }
+        hipLaunchKernelGGL((gemm_slicek_bf16<NT, TILES, false>), grid, block, lds, st, a);
+    }
+    hipLaunchKernelGGL((gemm_fixup_bf16<NT, EPI>), dim3((p.tasks + 3) / 4), dim3(256), 0, st, a);
 }
 
 template <int NT>
@@ -417,12 +685,19 @@ void launch_gemm_bf16(const GemmArgs &a0, hipStream_t st) {
         if (a0.ssq_out) a.ssq_out = a0.ssq_out + (size_t)r0 * (p.N / 16);
         if (a0.act_hi) { a.act_hi = (bf16_t *)a0.act_hi + (size_t)t0 * a0.act_KSp * 512; a.act_lo = (bf16_t *)a0.act_lo + (size_t)t0 * a0.act_KSp * 512; }
         if (a0.pval) { a.pval = a0.pval + (size_t)r0 * a0.n_part; a.pidx = a0.pidx + (size_t)r0 * a0.n_part; }
-        if (a0.row_pos) { a.row_pos = a0.row_pos + r0; a.row_slot = a0.row_slot + r0; }
+        if (a0.row_pos) { a.row_pos = a0.row_pos + r0; a.row_slot = a0.row_slot + r0; a.row_cs = a0.row_cs + (size_t)r0 * a0.dh; }
         if (a0.q_hi) { a.q_hi = (bf16_t *)a0.q_hi + (size_t)t0 * (a0.H * a0.dh / 32) * 512; a.q_lo = (bf16_t *)a0.q_lo + (size_t)t0 * (a0.H * a0.dh / 32) * 512; }
         if (rows <= 16) launch_gemm_nt<1>(a, st);
         else if (rows <= 32) launch_gemm_nt<2>(a, st);
         else launch_gemm_nt<3>(a, st);
     }
+}
+
+// waves per GEMM workgroup (LLMA_GEMM_W overrides, for experiments)
+static int gemm_wg_waves() {
+    const char *e = getenv("LLMA_GEMM_W");
+    int w = e ? atoi(e) : 8;
+    return (w == 4 || w == 8) ? w : 8;
 }
 
 // how a [N][K] matrix is cut: slices of ~16 k-steps (padding K up if needed), ~2048-4096 waves
@@ -448,7 +723,14 @@ GemmPlan make_gemm_plan(int N, int K, int tiles_per_task) {
     int tpw = (p.tasks + waves_per_slice - 1) / waves_per_slice;
     if (tpw < 1) tpw = 1;
     if (tiles_per_task == 2 && tpw > 2) tpw = (tpw + 1) / 2;
-    p.G = (p.tasks + 4 * tpw - 1) / (4 * tpw);
+    // single-kernel variant: tiles per workgroup so that the grid is about one or two workgroups
+    // per compute unit, 16 waves when a workgroup owns several tiles, else 8
+    p.tk_ft = (tiles_per_task == 2) ? 1 : (p.tasks >= 1536 ? 4 : (p.tasks >= 640 ? 3 : 1));
+    p.tk_waves = p.tk_ft > 1 ? 16 : 8;
+    { const char *e = getenv("LLMA_GEMM_TK"); if (e) p.tk_ft = atoi(e); const char *w = getenv("LLMA_GEMM_TKW"); if (w) p.tk_waves = atoi(w); }
+    p.W = gemm_wg_waves();
+    if (tpw > 1 && p.W > 4 && p.tasks < 4 * p.W * 64 / p.S) p.W = 4;
+    p.G = (p.tasks + p.W * tpw - 1) / (p.W * tpw);
     return p;
 }
 
@@ -456,10 +738,10 @@ GemmPlan make_gemm_plan(int N, int K, int tiles_per_task) {
 // causal attention of m <= 16*NTQ query rows of one sequence over its KV cache
 // =============================================================================================
 // grid = (chunks of ATTN_CHUNK key positions, heads, sequences); 4 waves per workgroup, wave w
-// owns the 64 positions [64 w, 64 w + 64) of the chunk as two groups of 32.  Per group:
-// S^T = K_tile . Q^T (MFMA, keys on the A side so the cache is read as whole 1 KiB blocks; with
-// hi/lo planes S = Khi.qhi + Khi.qlo + Klo.qhi), scale, causal mask by absolute position,
-// online softmax per query row, O^T += V^T . P^T (again hi/lo).  The four waves' (max, sum, O)
+// owns the 32 positions [32 w, 32 w + 32) of the chunk and issues all of their K and V loads
+// (whole 1 KiB blocks) before any arithmetic.  S^T = K_tile . Q^T (MFMA, keys on the A side;
+// with hi/lo planes S = Khi.qhi + Khi.qlo + Klo.qhi), scale, causal mask by absolute position,
+// softmax statistics per query row, O^T = V^T . P^T (again hi/lo).  The four waves' (max, sum, O)
 // are merged in wave order, and the chunk's partial is written for the combine kernel.  Which
 // keys a row sees, and in which order they are reduced, is a function of absolute positions only.
 template <int DH, int NTQ, bool KVS>
@@ -468,34 +750,42 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
     constexpr int DT = DH / 16;       // 16-feature tiles of the head dimension
     constexpr int RQ = NTQ * 16;
     __shared__ float sm[4][RQ], sl[4][RQ];
-    __shared__ float so[RQ][DH + 4];
+    __shared__ float so[4][RQ][DH + 4];
 
     const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 15, g = lane >> 4;
-    const int slot = a.batch_slots[b];
-    const int T = a.T[slot];
+    const int slot = a.slot_const >= 0 ? a.slot_const : a.batch_slots[b];
     const int m = a.m;
-    const int kv_len = T + m;
     const int chunk0 = c * ATTN_CHUNK;
-    if (chunk0 >= kv_len) return;                       // uniform for the workgroup
     const int d_model = a.H * DH;
-
-    u32x4 qh[NTQ][KSTEPS], ql[NTQ][KSTEPS];
-    int rpos[NTQ];
+    const int key0 = chunk0 + wave * 32;
+    const size_t head_base = ((size_t)slot * a.H + h) * (size_t)a.max_seq * DH;
+    // K and V blocks of the wave's 32 positions: issued before the sequence length is known (any
+    // position below max_seq lies inside the cache allocation; unused blocks are simply dropped)
+    u32x4 ka[2][KSTEPS], kb[2][KSTEPS], va[DT], vb[DT];
+    {
+        const bf16_t *kh = (const bf16_t *)a.Khi + head_base, *kl = (const bf16_t *)a.Klo + head_base;
+        const bf16_t *vh = (const bf16_t *)a.Vhi + head_base, *vl = (const bf16_t *)a.Vlo + head_base;
 #pragma unroll
-    for (int q = 0; q < NTQ; ++q) {
-        const int j = q * 16 + n;
-        const bool valid = j < m;
-        rpos[q] = valid ? T + j : -1;
-        const int r = b * m + (valid ? j : 0);
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int s = 0; s < KSTEPS; ++s) {
-            const size_t o = xtile_off(r, h * DH + s * 32 + g * 8, d_model / 32);
-            qh[q][s] = *(const u32x4 *)((const bf16_t *)a.Qhi + o);
-            ql[q][s] = *(const u32x4 *)((const bf16_t *)a.Qlo + o);
+            for (int s = 0; s < KSTEPS; ++s) {
+                const size_t off = (size_t)(key0 / 16 + t) * (16 * DH) + s * 512 + lane * 8;
+                ka[t][s] = *(const u32x4 *)(kh + off);
+                if (KVS) kb[t][s] = *(const u32x4 *)(kl + off);
+            }
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            const size_t off = (size_t)(key0 / 32) * (32 * DH) + dt * 512 + lane * 8;
+            va[dt] = *(const u32x4 *)(vh + off);
+            if (KVS) vb[dt] = *(const u32x4 *)(vl + off);
         }
     }
+    const int T = a.T[slot];
+    const int kv_len = T + m;
+    if (chunk0 >= kv_len) return;                       // uniform for the workgroup
+    const bool active = key0 < kv_len;                  // uniform for the wave
 
     float mrow[NTQ], lrow[NTQ];
     f32x4 o[NTQ][DT];
@@ -507,124 +797,91 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
         for (int dt = 0; dt < DT; ++dt) o[q][dt] = (f32x4){0.f, 0.f, 0.f, 0.f};
     }
 
-    const size_t head_base = ((size_t)slot * a.H + h) * (size_t)a.max_seq * DH;
-    const bf16_t *kh = (const bf16_t *)a.Khi + head_base, *kl = (const bf16_t *)a.Klo + head_base;
-    const bf16_t *vh = (const bf16_t *)a.Vhi + head_base, *vl = (const bf16_t *)a.Vlo + head_base;
-
-#pragma unroll 1
-    for (int gi = 0; gi < 2; ++gi) {
-        const int key0 = chunk0 + (wave * 2 + gi) * 32;
-        if (key0 >= kv_len) break;                      // uniform for the wave
-        f32x4 s2[NTQ][2];
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            u32x4 ka[KSTEPS], kb[KSTEPS];
-#pragma unroll
-            for (int s = 0; s < KSTEPS; ++s) {
-                const size_t off = (size_t)(key0 / 16 + t) * (16 * DH) + s * 512 + lane * 8;
-                ka[s] = *(const u32x4 *)(kh + off);
-                if (KVS) kb[s] = *(const u32x4 *)(kl + off);
-            }
-#pragma unroll
-            for (int q = 0; q < NTQ; ++q) {
-                f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int s = 0; s < KSTEPS; ++s) {
-                    acc = mfma16x16x32(ka[s], qh[q][s], acc);
-                    acc = mfma16x16x32(ka[s], ql[q][s], acc);
-                    if (KVS) acc = mfma16x16x32(kb[s], qh[q][s], acc);
-                }
-                s2[q][t] = acc;
-            }
-        }
-        u32x4 ph[NTQ], pl[NTQ];
+    if (active) {
 #pragma unroll
         for (int q = 0; q < NTQ; ++q) {
+            const int j = q * 16 + n;
+            const bool valid = j < m;
+            const int rpos = valid ? T + j : -1;
+            const int r = b * m + (valid ? j : 0);
+            u32x4 qh[KSTEPS], ql[KSTEPS];
+#pragma unroll
+            for (int s = 0; s < KSTEPS; ++s) {
+                const size_t off = xtile_off(r, h * DH + s * 32 + g * 8, d_model / 32);
+                qh[s] = *(const u32x4 *)((const bf16_t *)a.Qhi + off);
+                ql[s] = *(const u32x4 *)((const bf16_t *)a.Qlo + off);
+            }
             float sv[8];
             float mx = LLMA_NEG_INF;
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
+            for (int t = 0; t < 2; ++t) {
+                f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int key = key0 + t * 16 + 4 * g + r;
-                    float v = s2[q][t][r] * a.scale;
-                    v = (key > rpos[q]) ? LLMA_NEG_INF : v;
-                    sv[t * 4 + r] = v;
+                for (int s = 0; s < KSTEPS; ++s) {
+                    acc = mfma16x16x32(ka[t][s], qh[s], acc);
+                    acc = mfma16x16x32(ka[t][s], ql[s], acc);
+                    if (KVS) acc = mfma16x16x32(kb[t][s], qh[s], acc);
+                }
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int key = key0 + t * 16 + 4 * g + r4;
+                    float v = acc[r4] * a.scale;
+                    v = (key > rpos) ? LLMA_NEG_INF : v;
+                    sv[t * 4 + r4] = v;
                     mx = fmaxf(mx, v);
                 }
+            }
             mx = fmaxf(mx, __shfl_xor(mx, 16));
             mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float mnew = fmaxf(mrow[q], mx);
-            float alpha = 1.f, psum = 0.f;
+            float psum = 0.f;
             float p[8];
-            if (mnew == LLMA_NEG_INF) {
 #pragma unroll
-                for (int i = 0; i < 8; ++i) p[i] = 0.f;
-            } else {
-                alpha = __expf(mrow[q] - mnew);          // exp(-inf) = 0 on the first visible group
-#pragma unroll
-                for (int i = 0; i < 8; ++i) { p[i] = __expf(sv[i] - mnew); psum += p[i]; }
+            for (int i = 0; i < 8; ++i) {
+                p[i] = (mx == LLMA_NEG_INF) ? 0.f : __expf(sv[i] - mx);
+                psum += p[i];
             }
-            lrow[q] = lrow[q] * alpha + psum;
-            mrow[q] = mnew;
+            lrow[q] = psum;
+            mrow[q] = mx;
             u32x2 h0, l0, h1, l1;
             split4(p, h0, l0);
             split4(p + 4, h1, l1);
-            ph[q] = (u32x4){h0[0], h0[1], h1[0], h1[1]};
-            pl[q] = (u32x4){l0[0], l0[1], l1[0], l1[1]};
+            const u32x4 ph = (u32x4){h0[0], h0[1], h1[0], h1[1]};
+            const u32x4 pl = (u32x4){l0[0], l0[1], l1[0], l1[1]};
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt) o[q][dt] = o[q][dt] * alpha;
-        }
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-            const size_t off = (size_t)(key0 / 32) * (32 * DH) + dt * 512 + lane * 8;
-            const u32x4 va = *(const u32x4 *)(vh + off);
-            u32x4 vb;
-            if (KVS) vb = *(const u32x4 *)(vl + off);
-#pragma unroll
-            for (int q = 0; q < NTQ; ++q) {
-                o[q][dt] = mfma16x16x32(va, ph[q], o[q][dt]);
-                o[q][dt] = mfma16x16x32(va, pl[q], o[q][dt]);
-                if (KVS) o[q][dt] = mfma16x16x32(vb, ph[q], o[q][dt]);
+            for (int dt = 0; dt < DT; ++dt) {
+                o[q][dt] = mfma16x16x32(va[dt], ph, o[q][dt]);
+                o[q][dt] = mfma16x16x32(va[dt], pl, o[q][dt]);
+                if (KVS) o[q][dt] = mfma16x16x32(vb[dt], ph, o[q][dt]);
             }
         }
     }
 
-    // ---- merge the four waves in wave order ----
+    // ---- merge the four waves in wave order: every wave publishes (max, sum, O), then all
+    //      threads add the four contributions e^{m_w - M} O_w of an output element in wave order
 #pragma unroll
     for (int q = 0; q < NTQ; ++q) {
         float l = lrow[q];
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
-        lrow[q] = l;
         if (g == 0) { sm[wave][q * 16 + n] = mrow[q]; sl[wave][q * 16 + n] = l; }
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) *(f32x4 *)&so[wave][q * 16 + n][dt * 16 + 4 * g] = o[q][dt];
     }
     __syncthreads();
-    float scale_w[NTQ];
-#pragma unroll
-    for (int q = 0; q < NTQ; ++q) {
-        float M = LLMA_NEG_INF;
-        for (int w = 0; w < 4; ++w) M = fmaxf(M, sm[w][q * 16 + n]);
-        scale_w[q] = (mrow[q] == LLMA_NEG_INF) ? 0.f : __expf(mrow[q] - M);
-    }
-    for (int w = 0; w < 4; ++w) {
-        if (wave == w) {
-#pragma unroll
-            for (int q = 0; q < NTQ; ++q)
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt) {
-                    f32x4 v = o[q][dt] * scale_w[q];
-                    f32x4 *p = (f32x4 *)&so[q * 16 + n][dt * 16 + 4 * g];
-                    if (w == 0) *p = v; else *p = *p + v;
-                }
-        }
-        __syncthreads();
-    }
-    // ---- write the chunk partial: rows j < m ----
     const size_t pbase = (((size_t)b * a.H + h) * a.n_chunks + c) * RQ;
-    for (int idx = threadIdx.x; idx < m * DH; idx += 256) {
-        int j = idx / DH, d = idx % DH;
-        a.po[(pbase + j) * DH + d] = so[j][d];
+    for (int idx = threadIdx.x; idx < m * (DH / 4); idx += 256) {
+        const int j = idx / (DH / 4), d4 = idx % (DH / 4);
+        float M = LLMA_NEG_INF;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) M = fmaxf(M, sm[w][j]);
+        f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float mw = sm[w][j];
+            const float sc = (mw == LLMA_NEG_INF) ? 0.f : __expf(mw - M);
+            acc += *(const f32x4 *)&so[w][j][d4 * 4] * sc;
+        }
+        *(f32x4 *)(a.po + (pbase + j) * DH + d4 * 4) = acc;
     }
     if (threadIdx.x < m) {
         int j = threadIdx.x;
@@ -641,7 +898,8 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
 }
 
 // merges the chunk partials of one (row, head): out = sum_c e^{m_c - M} O_c / sum_c e^{m_c - M} l_c,
-// over the chunks that contain positions <= the row's own, in chunk order; writes hi/lo tiled planes
+// over the chunks that contain positions <= the row's own, in chunk order; writes hi/lo tiled planes.
+// One thread per 4 output features; loads are issued 8 chunks at a time.
 template <int DH>
 __global__ void attn_combine_bf16_kernel(AttnArgs a, int rq) {
     const int r = blockIdx.x, h = blockIdx.y;
@@ -649,22 +907,42 @@ __global__ void attn_combine_bf16_kernel(AttnArgs a, int rq) {
     const int slot = a.batch_slots[b];
     const int pos = a.T[slot] + j;
     const int nc = pos / ATTN_CHUNK + 1;
-    const int d = threadIdx.x;
+    const int d4 = threadIdx.x;                        // features 4 d4 .. +3
     const size_t base = ((size_t)b * a.H + h) * a.n_chunks;
     float M = LLMA_NEG_INF;
-    for (int c = 0; c < nc; ++c) M = fmaxf(M, a.pm[(base + c) * rq + j]);
-    float L = 0.f, acc = 0.f;
-    for (int c = 0; c < nc; ++c) {
-        float w = __expf(a.pm[(base + c) * rq + j] - M);
-        L += w * a.pl[(base + c) * rq + j];
-        acc += w * a.po[((base + c) * rq + j) * DH + d];
+    for (int c0 = 0; c0 < nc; c0 += 8) {
+        float mv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) mv[u] = (c0 + u < nc) ? a.pm[(base + c0 + u) * rq + j] : LLMA_NEG_INF;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) M = fmaxf(M, mv[u]);
     }
-    float v = acc / L;
-    bf16_t hi, lo;
-    split_bf16(v, hi, lo);
-    const size_t o = xtile_off(r, h * DH + d, a.out_KSp);
-    ((bf16_t *)a.out_hi)[o] = hi;
-    ((bf16_t *)a.out_lo)[o] = lo;
+    float L = 0.f;
+    f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int c0 = 0; c0 < nc; c0 += 8) {
+        float mv[8], lv[8];
+        f32x4 ov[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (c0 + u < nc) {
+                mv[u] = a.pm[(base + c0 + u) * rq + j];
+                lv[u] = a.pl[(base + c0 + u) * rq + j];
+                ov[u] = *(const f32x4 *)(a.po + ((base + c0 + u) * rq + j) * DH + d4 * 4);
+            }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (c0 + u < nc) {
+                const float w = __expf(mv[u] - M);
+                L += w * lv[u];
+                acc += ov[u] * w;
+            }
+    }
+    float v[4] = {acc[0] / L, acc[1] / L, acc[2] / L, acc[3] / L};
+    u32x2 hi, lo;
+    split4(v, hi, lo);
+    const size_t o = xtile_off(r, h * DH + d4 * 4, a.out_KSp);
+    *(u32x2 *)((bf16_t *)a.out_hi + o) = hi;
+    *(u32x2 *)((bf16_t *)a.out_lo + o) = lo;
 }
 
 template <int DH, bool KVS>
@@ -674,7 +952,7 @@ static void launch_attn_dh(const AttnArgs &a, hipStream_t st) {
     if (ntq == 1) hipLaunchKernelGGL((attn_bf16_kernel<DH, 1, KVS>), grid, dim3(256), 0, st, a);
     else if (ntq == 2) hipLaunchKernelGGL((attn_bf16_kernel<DH, 2, KVS>), grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL((attn_bf16_kernel<DH, 3, KVS>), grid, dim3(256), 0, st, a);
-    hipLaunchKernelGGL((attn_combine_bf16_kernel<DH>), dim3(a.n_seqs * a.m, a.H), dim3(DH), 0, st, a, ntq * 16);
+    hipLaunchKernelGGL((attn_combine_bf16_kernel<DH>), dim3(a.n_seqs * a.m, a.H), dim3(DH / 4), 0, st, a, ntq * 16);
 }
 
 void launch_attn_bf16(const AttnArgs &a, hipStream_t st) {

@@ -8,33 +8,40 @@
 // ---------------------------------------------------------------------------------------------
 // row set-up
 // ---------------------------------------------------------------------------------------------
-__global__ void setup_step_rows_kernel(StepState s, int n_seqs, int m, int max_k) {
-    int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= n_seqs * m) return;
-    int b = idx / m, j = idx % m;
-    int slot = s.batch_slots[b];
-    int tok;
-    if (j == 0) tok = s.pending[slot];
-    else tok = (j - 1 < s.keff[b]) ? s.draft[b * max_k + j - 1] : 0;   // rows past keff are padding
-    s.row_tok[idx] = tok;
-    s.row_pos[idx] = s.T[slot] + j;
-    s.row_slot[idx] = slot;
+// one workgroup per row; also copies the row's rotary (cos, sin) pairs out of the position table
+__global__ void setup_step_rows_kernel(StepState s, int m, int max_k, const float *cs, int half) {
+    const int idx = blockIdx.x;
+    const int b = idx / m, j = idx % m;
+    const int slot = s.batch_slots[b];
+    const int pos = s.T[slot] + j;
+    if (threadIdx.x == 0) {
+        int tok;
+        if (j == 0) tok = s.pending[slot];
+        else tok = (j - 1 < s.keff[b]) ? s.draft[b * max_k + j - 1] : 0;   // rows past keff are padding
+        s.row_tok[idx] = tok;
+        s.row_pos[idx] = pos;
+        s.row_slot[idx] = slot;
+    }
+    for (int i = threadIdx.x; i < 2 * half; i += blockDim.x) s.row_cs[(size_t)idx * 2 * half + i] = cs[(size_t)pos * 2 * half + i];
 }
-void launch_setup_step_rows(const StepState &s, int n_seqs, int m, int max_k, hipStream_t st) {
-    int R = n_seqs * m;
-    hipLaunchKernelGGL(setup_step_rows_kernel, dim3((R + 63) / 64), dim3(64), 0, st, s, n_seqs, m, max_k);
+void launch_setup_step_rows(const StepState &s, int n_seqs, int m, int max_k, const float *cs, int half, hipStream_t st) {
+    hipLaunchKernelGGL(setup_step_rows_kernel, dim3(n_seqs * m), dim3(64), 0, st, s, m, max_k, cs, half);
 }
 
-__global__ void setup_prefill_rows_kernel(StepState s, const int *prompt, int off, int m, int slot) {
-    int j = threadIdx.x;
-    if (j >= m) return;
-    s.row_tok[j] = prompt[off + j];
-    s.row_pos[j] = s.T[slot] + j;
-    s.row_slot[j] = slot;
-    if (j == 0) s.batch_slots[0] = slot;
+__global__ void setup_prefill_rows_kernel(StepState s, const int *prompt, const int *base, int slot, const float *cs, int half) {
+    const int j = blockIdx.x;
+    const int pos = s.T[slot] + j;
+    if (threadIdx.x == 0) {
+        s.row_tok[j] = prompt[pos - *base];
+        s.row_pos[j] = pos;
+        s.row_slot[j] = slot;
+        if (j == 0) s.batch_slots[0] = slot;
+    }
+    for (int i = threadIdx.x; i < 2 * half; i += blockDim.x) s.row_cs[(size_t)j * 2 * half + i] = cs[(size_t)pos * 2 * half + i];
 }
-void launch_setup_prefill_rows(const StepState &s, const int *prompt_dev, int off, int m, int slot, hipStream_t st) {
-    hipLaunchKernelGGL(setup_prefill_rows_kernel, dim3(1), dim3(64), 0, st, s, prompt_dev, off, m, slot);
+void launch_setup_prefill_rows(const StepState &s, const int *prompt_dev, const int *base_dev, int m, int slot,
+                               const float *cs, int half, hipStream_t st) {
+    hipLaunchKernelGGL(setup_prefill_rows_kernel, dim3(m), dim3(64), 0, st, s, prompt_dev, base_dev, slot, cs, half);
 }
 
 __global__ void advance_T_kernel(StepState s, int slot, int by) { s.T[slot] += by; }

@@ -8,6 +8,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <map>
 #include <string>
 #include <utility>
 #include <vector>
@@ -18,13 +19,20 @@
 
 static thread_local std::string g_err;      // errors of calls that have no context
 
-#define PREFILL_ROWS 32
+#define PREFILL_ROWS 48
 
 struct EventPair { hipEvent_t a, b; };
 
+enum StepKind { STEP_PREFILL = 0, STEP_VERIFY = 1, STEP_GEN = 2 };
+
+struct GraphSlot { int seen = 0; hipGraphExec_t exec = nullptr; };
+
 struct llma_ctx {
     llma_model_cfg cfg;
-    hipStream_t st = nullptr;
+    hipStream_t st = nullptr;          // the caller's stream: everything is ordered on it
+    hipStream_t run_st = nullptr;      // where the launchers enqueue: st, or cap_st while capturing
+    hipStream_t cap_st = nullptr;      // private stream used only to capture step graphs
+    std::map<uint64_t, GraphSlot> graphs;
     bool bf16 = false;
     std::vector<void *> allocs;
     int64_t dev_bytes = 0;
@@ -35,7 +43,9 @@ struct llma_ctx {
     float *final_norm = nullptr;
     std::vector<void *> wqkv, wo, wgu, wd;
     std::vector<float *> n1, n2;
-    // KV cache per layer: [max_batch][H][max_seq][dh]; bf16 with kv_split: a second (lo) plane
+    // KV cache per layer: [max_batch][H][seq_cap][dh]; bf16 with kv_split: a second (lo) plane.
+    // seq_cap = max_seq rounded up to whole attention chunks, so a chunk's block loads never leave the allocation
+    int seq_cap = 0;
     std::vector<void *> kc, vc, kc_lo, vc_lo;
     float *cs_table = nullptr;
     bool kv_split = false;
@@ -46,10 +56,9 @@ struct llma_ctx {
     void *xhi = nullptr, *xlo = nullptr, *q = nullptr, *q_lo = nullptr, *att_hi = nullptr, *att_lo = nullptr, *act_hi = nullptr, *act_lo = nullptr;
     float *po = nullptr, *pm = nullptr, *pl = nullptr;
     int nc_max = 0;
-    // bf16 GEMM work division, partial-sum scratch, tickets, per-tile sums of squares
+    // bf16 GEMM work division, partial-sum scratch, per-tile sums of squares
     GemmPlan plan_qkv{}, plan_o{}, plan_gu{}, plan_down{}, plan_lm{};
     float *partial = nullptr, *ssq = nullptr;
-    int *ticket = nullptr;
     float *pval = nullptr;
     int *pidx = nullptr;
     int n_part = 0;
@@ -58,7 +67,7 @@ struct llma_ctx {
     GenState gen{};               // host copy (device pointers inside)
     GenState *gen_dev = nullptr;
     int *gen_prompt = nullptr, *gen_ref = nullptr, *gen_doc_offsets = nullptr, *gen_ref_doc = nullptr;
-    int *gen_y = nullptr, *gen_trace = nullptr, *gen_counters = nullptr;   // counters: n_out, n_steps, cur[2]
+    int *gen_y = nullptr, *gen_trace = nullptr, *gen_counters = nullptr;   // counters: n_out, n_steps, cur[2], prefill base
     int cap_prompt = 0, cap_ref = 0, cap_refdoc = 0, cap_docs = 0, cap_new = 0;
 
     std::vector<int> T_host, pending_host, import_mask_layers;
@@ -181,7 +190,8 @@ static int create_impl(llma_ctx *c, const llma_weights *w) {
         HIP_TRY(c, hipMemcpyAsync(c->n2[l], w->norm2[l], d * 4, hipMemcpyDeviceToDevice, c->st));
     }
     // ---- KV cache, zero-filled so that never-written positions hold finite values
-    const size_t kv_bytes = (size_t)g.max_batch * H * g.max_seq * dh * es;
+    c->seq_cap = (g.max_seq + ATTN_CHUNK - 1) / ATTN_CHUNK * ATTN_CHUNK;
+    const size_t kv_bytes = (size_t)g.max_batch * H * c->seq_cap * dh * es;
     for (int l = 0; l < L; ++l) {
         ALLOC(c, c->kc[l], kv_bytes);
         ALLOC(c, c->vc[l], kv_bytes);
@@ -226,16 +236,13 @@ static int create_impl(llma_ctx *c, const llma_weights *w) {
             return rc;
         if ((rc = zalloc((void **)&c->ssq, Rp * (d / 16) * 4))) return rc;
         size_t part = 0;
-        int max_tasks = 0;
         const GemmPlan *pl[] = {&c->plan_qkv, &c->plan_o, &c->plan_gu, &c->plan_down, &c->plan_lm};
         for (const GemmPlan *p : pl) {
             const size_t b = (size_t)p->tasks * p->S * (p == &c->plan_gu ? 2 : 1) * 3 * 1024;
             if (b > part) part = b;
-            if (p->tasks > max_tasks) max_tasks = p->tasks;
         }
         ALLOC(c, c->partial, part);
-        if ((rc = zalloc((void **)&c->ticket, (size_t)max_tasks * 4))) return rc;
-        c->nc_max = (g.max_seq + ATTN_CHUNK - 1) / ATTN_CHUNK;
+        c->nc_max = c->seq_cap / ATTN_CHUNK;
         const size_t np = (size_t)g.max_batch * H * c->nc_max * 48;
         ALLOC(c, c->po, np * dh * 4);
         ALLOC(c, c->pm, np * 4);
@@ -254,6 +261,8 @@ static int create_impl(llma_ctx *c, const llma_weights *w) {
     ALLOC(c, s.row_tok, Rp * 4);
     ALLOC(c, s.row_pos, Rp * 4);
     ALLOC(c, s.row_slot, Rp * 4);
+    ALLOC(c, s.row_cs, Rp * dh * 4);
+    HIP_TRY(c, hipMemsetAsync(s.row_cs, 0, Rp * dh * 4, c->st));
     ALLOC(c, s.T, g.max_batch * 4);
     ALLOC(c, s.pending, g.max_batch * 4);
     ALLOC(c, s.batch_slots, g.max_batch * 4);
@@ -269,10 +278,11 @@ static int create_impl(llma_ctx *c, const llma_weights *w) {
     HIP_TRY(c, hipMemsetAsync(s.row_pos, 0, Rp * 4, c->st));
     HIP_TRY(c, hipMemsetAsync(s.row_slot, 0, Rp * 4, c->st));
     ALLOC(c, c->gen_dev, sizeof(GenState));
-    ALLOC(c, c->gen_counters, 4 * 4);
+    ALLOC(c, c->gen_counters, 8 * 4);
     c->T_host.assign(g.max_batch, 0);
     c->pending_host.assign(g.max_batch, -1);
     c->import_mask_layers.assign(g.max_batch, 0);
+    HIP_TRY(c, hipStreamCreateWithFlags(&c->cap_st, hipStreamNonBlocking));
     HIP_TRY(c, hipStreamSynchronize(c->st));
     HIP_TRY(c, hipGetLastError());
     return LLMA_OK;
@@ -289,6 +299,7 @@ extern "C" int llma_create(const llma_model_cfg *cfg, const llma_weights *w, voi
     if (!c) return fail(nullptr, LLMA_E_NOMEM, "llma_create: host allocation failed");
     c->cfg = *cfg;
     c->st = (hipStream_t)hip_stream;
+    c->run_st = c->st;
     c->bf16 = cfg->dtype == LLMA_DTYPE_BF16;
     c->kv_split = c->bf16 && cfg->kv_split != 0;
     rc = create_impl(c, w);
@@ -305,6 +316,8 @@ extern "C" int llma_create(const llma_model_cfg *cfg, const llma_weights *w, voi
 extern "C" int llma_destroy(llma_ctx *c) {
     if (!c) return LLMA_OK;
     (void)hipStreamSynchronize(c->st);
+    for (auto &g : c->graphs) if (g.second.exec) (void)hipGraphExecDestroy(g.second.exec);
+    if (c->cap_st) (void)hipStreamDestroy(c->cap_st);
     for (auto &e : c->events) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
     for (void *p : c->allocs) (void)hipFree(p);
     delete c;
@@ -321,18 +334,18 @@ static int forward_f32(llma_ctx *c, int n_seqs, int m, bool lm_head) {
     const llma_model_cfg &g = c->cfg;
     const int d = g.d_model, F = g.d_ffn, V = g.vocab, H = g.n_heads, dh = g.head_dim, L = g.n_layers;
     const int R = n_seqs * m;
-    hipStream_t st = c->st;
+    hipStream_t st = c->run_st;
     launch_embed_f32((const float *)c->embed, c->s.row_tok, c->h, R, d, st);
     GemmArgs ga{};
     ga.rows = R;
     AttnArgs aa{};
-    aa.Qhi = c->q; aa.T = c->s.T; aa.batch_slots = c->s.batch_slots; aa.n_seqs = n_seqs; aa.m = m; aa.H = H; aa.dh = dh;
-    aa.max_seq = g.max_seq; aa.scale = 1.0f / sqrtf((float)dh); aa.out_hi = c->att_hi;
+    aa.Qhi = c->q; aa.T = c->s.T; aa.batch_slots = c->s.batch_slots; aa.slot_const = -1; aa.n_seqs = n_seqs; aa.m = m; aa.H = H; aa.dh = dh;
+    aa.max_seq = c->seq_cap; aa.scale = 1.0f / sqrtf((float)dh); aa.out_hi = c->att_hi;
     for (int l = 0; l < L; ++l) {
         launch_rmsnorm_f32(c->h, c->n1[l], g.rms_eps, (float *)c->xhi, R, d, st);
         ga.W = c->wqkv[l]; ga.Xhi = c->xhi; ga.N = 3 * d; ga.K = d; ga.epi = EPI_STORE; ga.out = c->qkv;
         launch_gemm_f32(ga, st);
-        launch_rope_kv_f32(c->qkv, c->s, c->cs_table, (float *)c->q, (float *)c->kc[l], (float *)c->vc[l], R, H, dh, g.max_seq, st);
+        launch_rope_kv_f32(c->qkv, c->s, c->cs_table, (float *)c->q, (float *)c->kc[l], (float *)c->vc[l], R, H, dh, c->seq_cap, st);
         aa.Khi = c->kc[l]; aa.Vhi = c->vc[l];
         launch_attn_f32(aa, st);
         ga.W = c->wo[l]; ga.Xhi = c->att_hi; ga.N = d; ga.K = d; ga.epi = EPI_RESID; ga.out = c->h;
@@ -355,24 +368,25 @@ static int forward_f32(llma_ctx *c, int n_seqs, int m, bool lm_head) {
 
 // bf16: per layer  QKV GEMM (+RMSNorm scale, RoPE, KV append) -> attention -> O GEMM (+residual,
 // next-norm input) -> gate/up GEMM (+RMSNorm scale, SwiGLU) -> down GEMM (+residual, next-norm input)
-static int forward_bf16(llma_ctx *c, int n_seqs, int m, int t_max, bool lm_head) {
+static int forward_bf16(llma_ctx *c, int n_seqs, int m, int n_chunks, bool lm_head, int slot) {
     const llma_model_cfg &g = c->cfg;
     const int d = g.d_model, H = g.n_heads, dh = g.head_dim, L = g.n_layers;
     const int R = n_seqs * m;
-    hipStream_t st = c->st;
+    hipStream_t st = c->run_st;
     const int ksp_d = c->plan_qkv.KSp;          // k-steps per row tile of every activation plane that feeds a K = d GEMM
     launch_embed_prep_bf16(c->embed, c->s.row_tok, c->n1[0], c->h, c->xhi, c->xlo, c->ssq, R, d, ksp_d, st);
     GemmArgs base{};
-    base.rows = R; base.split = c->opt_split; base.partial = c->partial; base.ticket = c->ticket; base.eps = g.rms_eps;
-    base.ssq_tiles = d / 16; base.H = H; base.dh = dh; base.max_seq = g.max_seq; base.nx_KSp = ksp_d;
+    base.rows = R; base.split = c->opt_split; base.partial = c->partial; base.eps = g.rms_eps;
+    base.tilek = lm_head ? 1 : 0;               // prompt chunks (no LM head) use the LDS-staged two-kernel variant
+    base.ssq_tiles = d / 16; base.H = H; base.dh = dh; base.max_seq = c->seq_cap; base.nx_KSp = ksp_d;
     AttnArgs aa{};
-    aa.Qhi = c->q; aa.Qlo = c->q_lo; aa.T = c->s.T; aa.batch_slots = c->s.batch_slots; aa.n_seqs = n_seqs; aa.m = m; aa.H = H; aa.dh = dh;
-    aa.max_seq = g.max_seq; aa.n_chunks = (t_max + m + ATTN_CHUNK - 1) / ATTN_CHUNK; aa.scale = 1.0f / sqrtf((float)dh);
+    aa.Qhi = c->q; aa.Qlo = c->q_lo; aa.T = c->s.T; aa.batch_slots = c->s.batch_slots; aa.slot_const = n_seqs == 1 ? slot : -1; aa.n_seqs = n_seqs; aa.m = m; aa.H = H; aa.dh = dh;
+    aa.max_seq = c->seq_cap; aa.n_chunks = n_chunks; aa.scale = 1.0f / sqrtf((float)dh);
     aa.po = c->po; aa.pm = c->pm; aa.pl = c->pl; aa.out_hi = c->att_hi; aa.out_lo = c->att_lo; aa.out_KSp = ksp_d;
     for (int l = 0; l < L; ++l) {
         GemmArgs ga = base;
         ga.W = c->wqkv[l]; ga.plan = c->plan_qkv; ga.Xhi = c->xhi; ga.Xlo = c->xlo; ga.epi = EPI_QKV; ga.ssq_in = c->ssq;
-        ga.row_pos = c->s.row_pos; ga.row_slot = c->s.row_slot; ga.cs = c->cs_table; ga.q_hi = c->q; ga.q_lo = c->q_lo;
+        ga.row_pos = c->s.row_pos; ga.row_slot = c->s.row_slot; ga.row_cs = c->s.row_cs; ga.q_hi = c->q; ga.q_lo = c->q_lo;
         ga.k_hi = c->kc[l]; ga.k_lo = c->kc_lo[l]; ga.v_hi = c->vc[l]; ga.v_lo = c->vc_lo[l];
         launch_gemm_bf16(ga, st);
         aa.Khi = c->kc[l]; aa.Klo = c->kc_lo[l]; aa.Vhi = c->vc[l]; aa.Vlo = c->vc_lo[l];
@@ -410,8 +424,64 @@ static int forward_bf16(llma_ctx *c, int n_seqs, int m, int t_max, bool lm_head)
     return LLMA_OK;
 }
 
-static int forward(llma_ctx *c, int n_seqs, int m, int t_max, bool lm_head) {
-    return c->bf16 ? forward_bf16(c, n_seqs, m, t_max, lm_head) : forward_f32(c, n_seqs, m, lm_head);
+static int forward(llma_ctx *c, int n_seqs, int m, int n_chunks, bool lm_head, int slot) {
+    return c->bf16 ? forward_bf16(c, n_seqs, m, n_chunks, lm_head, slot) : forward_f32(c, n_seqs, m, lm_head);
+}
+
+// One step = row set-up + forward + bookkeeping, always the same launches for a given
+// (kind, rows, attention chunk count, slot): the second time a shape is seen its launches are
+// captured into a HIP graph and from then on replayed.  All per-step data (tokens, positions,
+// cache lengths, drafts) lives in device memory, so a replay needs no new arguments.
+static int step_body(llma_ctx *c, int kind, int n_seqs, int m, int n_chunks, int slot) {
+    hipStream_t st = c->run_st;
+    const int mk = c->cfg.max_k;
+    if (kind == STEP_PREFILL) {
+        launch_setup_prefill_rows(c->s, c->gen_prompt, c->gen_counters + 4, m, slot, c->cs_table, c->cfg.head_dim / 2, st);
+        int rc = forward(c, 1, m, n_chunks, false, slot);
+        if (rc) return rc;
+        launch_advance_T(c->s, slot, m, st);
+        return LLMA_OK;
+    }
+    if (kind == STEP_GEN) launch_trigger(c->gen_dev, c->s, mk, st);
+    launch_setup_step_rows(c->s, n_seqs, m, mk, c->cs_table, c->cfg.head_dim / 2, st);
+    int rc = forward(c, n_seqs, m, n_chunks, true, slot);
+    if (rc) return rc;
+    launch_argmax_accept(c->pval, c->pidx, c->n_part, c->s, n_seqs, m, mk, kind == STEP_GEN ? c->gen_dev : nullptr, st);
+    return LLMA_OK;
+}
+
+static void drop_graphs(llma_ctx *c) {
+    (void)hipStreamSynchronize(c->st);
+    for (auto &g : c->graphs) if (g.second.exec) (void)hipGraphExecDestroy(g.second.exec);
+    c->graphs.clear();
+}
+
+static int run_step(llma_ctx *c, int kind, int n_seqs, int m, int t_max, int slot) {
+    // attention chunks launched: enough for the longest sequence, in buckets of 4 so that the
+    // launch shape (and with it the graph) changes only every 4 * ATTN_CHUNK positions
+    int n_chunks = (t_max + m + ATTN_CHUNK - 1) / ATTN_CHUNK;
+    n_chunks = (n_chunks + 3) / 4 * 4;
+    if (c->bf16 && n_chunks > c->nc_max) n_chunks = c->nc_max;
+    c->run_st = c->st;
+    if (!c->opt_graph || c->opt_timing || c->graphs.size() > 256) return step_body(c, kind, n_seqs, m, n_chunks, slot);
+    const uint64_t key = ((uint64_t)kind << 60) | ((uint64_t)n_seqs << 48) | ((uint64_t)m << 40) | ((uint64_t)n_chunks << 20) | (uint64_t)slot;
+    GraphSlot &gs = c->graphs[key];
+    if (gs.exec == nullptr) {
+        if (gs.seen++ == 0) return step_body(c, kind, n_seqs, m, n_chunks, slot);   // first time eagerly
+        hipGraph_t graph = nullptr;
+        if (hipStreamBeginCapture(c->cap_st, hipStreamCaptureModeRelaxed) != hipSuccess) { c->opt_graph = 0; return step_body(c, kind, n_seqs, m, n_chunks, slot); }
+        c->run_st = c->cap_st;
+        int rc = step_body(c, kind, n_seqs, m, n_chunks, slot);
+        c->run_st = c->st;
+        hipError_t e = hipStreamEndCapture(c->cap_st, &graph);
+        if (rc) { if (graph) (void)hipGraphDestroy(graph); return rc; }
+        if (e != hipSuccess || graph == nullptr) return fail(c, LLMA_E_HIP, "graph capture failed: %s", hipGetErrorString(e));
+        e = hipGraphInstantiate(&gs.exec, graph, nullptr, nullptr, 0);
+        (void)hipGraphDestroy(graph);
+        if (e != hipSuccess) { gs.exec = nullptr; return fail(c, LLMA_E_HIP, "hipGraphInstantiate: %s", hipGetErrorString(e)); }
+    }
+    HIP_TRY(c, hipGraphLaunch(gs.exec, c->st));
+    return LLMA_OK;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -466,12 +536,12 @@ extern "C" int llma_kv_import(llma_ctx *c, int32_t seq, int32_t layer, const voi
     if (len < 0 || len > c->cfg.max_seq) return fail(c, LLMA_E_RANGE, "llma_kv_import: len %d > max_seq %d", len, c->cfg.max_seq);
     const llma_model_cfg &g = c->cfg;
     const size_t es = c->bf16 ? 2 : 4;
-    const size_t slot_off = (size_t)seq * g.n_heads * g.max_seq * g.head_dim * es;
+    const size_t slot_off = (size_t)seq * g.n_heads * c->seq_cap * g.head_dim * es;
     void *kc = (char *)c->kc[layer] + slot_off, *vc = (char *)c->vc[layer] + slot_off;
     void *kl = c->kv_split ? (char *)c->kc_lo[layer] + slot_off : nullptr, *vl = c->kv_split ? (char *)c->vc_lo[layer] + slot_off : nullptr;
     if (len > 0) {
-        if (c->bf16) launch_kv_import_bf16(k, v, kc, kl, vc, vl, g.n_heads, len, g.head_dim, g.max_seq, c->st);
-        else launch_kv_import_f32(k, v, kc, vc, g.n_heads, len, g.head_dim, g.max_seq, c->st);
+        if (c->bf16) launch_kv_import_bf16(k, v, kc, kl, vc, vl, g.n_heads, len, g.head_dim, c->seq_cap, c->st);
+        else launch_kv_import_f32(k, v, kc, vc, g.n_heads, len, g.head_dim, c->seq_cap, c->st);
     }
     HIP_TRY(c, hipGetLastError());
     if (layer == g.n_layers - 1) {
@@ -488,13 +558,15 @@ static int check_tokens(llma_ctx *c, const int32_t *t, int n, const char *who) {
 }
 
 // feeds prompt_dev[0..len-1) in chunks; rows only write KV, no LM head
-static int prefill_rows(llma_ctx *c, int seq, const int *prompt_dev, int n_feed) {
+// feeds gen_prompt[0..n_feed) in chunks on top of the slot's cache; rows only write KV, no LM head
+static int prefill_rows(llma_ctx *c, int seq, int n_feed) {
+    // the chunk's tokens are gen_prompt[T - base ..]: base = T at the start of the prompt
+    HIP_TRY(c, hipMemcpyAsync(c->gen_counters + 4, &c->T_host[seq], 4, hipMemcpyHostToDevice, c->st));
+    HIP_TRY(c, hipStreamSynchronize(c->st));
     for (int off = 0; off < n_feed; off += PREFILL_ROWS) {
         const int m = n_feed - off < PREFILL_ROWS ? n_feed - off : PREFILL_ROWS;
-        launch_setup_prefill_rows(c->s, prompt_dev, off, m, seq, c->st);
-        int rc = forward(c, 1, m, c->T_host[seq], false);
+        int rc = run_step(c, STEP_PREFILL, 1, m, c->T_host[seq], seq);
         if (rc) return rc;
-        launch_advance_T(c->s, seq, m, c->st);
         c->T_host[seq] += m;
     }
     return LLMA_OK;
@@ -502,7 +574,7 @@ static int prefill_rows(llma_ctx *c, int seq, const int *prompt_dev, int n_feed)
 
 static int ensure_cap(llma_ctx *c, int **buf, int *cap, int need) {
     if (need <= *cap) return LLMA_OK;
-    HIP_TRY(c, hipStreamSynchronize(c->st));
+    drop_graphs(c);                                   // captured launches hold the old pointer
     if (*buf) { dev_free_one(c, *buf); *buf = nullptr; *cap = 0; }
     int ncap = need + need / 2 + 64;
     ALLOC(c, *buf, (size_t)ncap * 4);
@@ -519,7 +591,7 @@ extern "C" int llma_prefill(llma_ctx *c, int32_t seq, const int32_t *prompt, int
     if ((rc = check_tokens(c, prompt, len, "llma_prefill"))) return rc;
     if ((rc = ensure_cap(c, &c->gen_prompt, &c->cap_prompt, len))) return rc;
     HIP_TRY(c, hipMemcpyAsync(c->gen_prompt, prompt, (size_t)len * 4, hipMemcpyHostToDevice, c->st));
-    if ((rc = prefill_rows(c, seq, c->gen_prompt, len - 1))) return rc;
+    if ((rc = prefill_rows(c, seq, len - 1))) return rc;
     c->pending_host[seq] = prompt[len - 1];
     HIP_TRY(c, hipMemcpyAsync(c->s.pending + seq, &c->pending_host[seq], 4, hipMemcpyHostToDevice, c->st));
     HIP_TRY(c, hipStreamSynchronize(c->st));
@@ -598,10 +670,8 @@ extern "C" int llma_verify_step_batch(llma_ctx *c, int32_t n_seqs, const int32_t
     HIP_TRY(c, hipMemcpyAsync(c->s.batch_slots, seqs, (size_t)n_seqs * 4, hipMemcpyHostToDevice, st));
     HIP_TRY(c, hipMemcpyAsync(c->s.keff, keff.data(), (size_t)n_seqs * 4, hipMemcpyHostToDevice, st));
     if (k > 0) HIP_TRY(c, hipMemcpyAsync(c->s.draft, dr.data(), (size_t)n_seqs * mk * 4, hipMemcpyHostToDevice, st));
-    launch_setup_step_rows(c->s, n_seqs, m, mk, st);
-    int rc = forward(c, n_seqs, m, t_max, true);
+    int rc = run_step(c, STEP_VERIFY, n_seqs, m, t_max, n_seqs == 1 ? seqs[0] : 0);
     if (rc) return rc;
-    launch_argmax_accept(c->pval, c->pidx, c->n_part, c->s, n_seqs, m, mk, nullptr, st);
     std::vector<int> nacc(n_seqs), nxt(n_seqs), em((size_t)n_seqs * (mk + 1));
     HIP_TRY(c, hipMemcpyAsync(nacc.data(), c->s.nacc, (size_t)n_seqs * 4, hipMemcpyDeviceToHost, st));
     HIP_TRY(c, hipMemcpyAsync(nxt.data(), c->s.next, (size_t)n_seqs * 4, hipMemcpyDeviceToHost, st));
@@ -681,18 +751,15 @@ extern "C" int llma_generate(llma_ctx *c, int32_t seq, const int32_t *prompt, in
     c->pending_host[seq] = prompt[prompt_len - 1];
     c->import_mask_layers[seq] = 0;
     if ((rc = push_state(c, seq))) return rc;
-    if ((rc = prefill_rows(c, seq, c->gen_prompt, prompt_len - 1))) return rc;
+    if ((rc = prefill_rows(c, seq, prompt_len - 1))) return rc;
 
     // ---- the decoding loop: trigger -> rows -> forward -> accept, all on the device; the host
     //      only reads the output count back to know when to stop
-    const int m = k + 1, mk = g.max_k;
+    const int m = k + 1;
     HIP_TRY(c, hipMemcpyAsync(c->s.batch_slots, &seq, 4, hipMemcpyHostToDevice, st));
     int produced = 0, steps = 0;
     while (produced < max_new) {
-        launch_trigger(c->gen_dev, c->s, mk, st);
-        launch_setup_step_rows(c->s, 1, m, mk, st);
-        if ((rc = forward(c, 1, m, c->T_host[seq], true))) return rc;
-        launch_argmax_accept(c->pval, c->pidx, c->n_part, c->s, 1, m, mk, c->gen_dev, st);
+        if ((rc = run_step(c, STEP_GEN, 1, m, c->T_host[seq], seq))) return rc;
         int now = 0;
         HIP_TRY(c, hipMemcpyAsync(&now, G.n_out, 4, hipMemcpyDeviceToHost, st));
         HIP_TRY(c, hipStreamSynchronize(st));
@@ -716,6 +783,7 @@ extern "C" int llma_generate(llma_ctx *c, int32_t seq, const int32_t *prompt, in
 extern "C" int llma_set_logits_dump(llma_ctx *c, float *dev_buf, int32_t capacity_rows) {
     if (!c) return fail(nullptr, LLMA_E_INVAL, "llma_set_logits_dump: null context");
     if (dev_buf && capacity_rows < 1) return fail(c, LLMA_E_INVAL, "llma_set_logits_dump: capacity_rows < 1");
+    drop_graphs(c);
     c->logits_dump = dev_buf;
     c->dump_rows = dev_buf ? capacity_rows : 0;
     return LLMA_OK;
@@ -724,7 +792,7 @@ extern "C" int llma_set_logits_dump(llma_ctx *c, float *dev_buf, int32_t capacit
 extern "C" int llma_set_option(llma_ctx *c, int32_t option, int32_t value) {
     if (!c) return fail(nullptr, LLMA_E_INVAL, "llma_set_option: null context");
     switch (option) {
-        case LLMA_OPT_ACT_SPLIT: c->opt_split = value ? 1 : 0; return LLMA_OK;
+        case LLMA_OPT_ACT_SPLIT: drop_graphs(c); c->opt_split = value ? 1 : 0; return LLMA_OK;
         case LLMA_OPT_KERNEL_TIMING: c->opt_timing = value ? 1 : 0; return LLMA_OK;
         case LLMA_OPT_USE_GRAPH: c->opt_graph = value ? 1 : 0; return LLMA_OK;
         default: return fail(c, LLMA_E_INVAL, "llma_set_option: unknown option %d", option);

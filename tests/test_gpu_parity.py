@@ -132,26 +132,75 @@ def test_verify_step_logits_and_state(llma, cfg):
     ctx.close()
 
 
+@pytest.mark.parametrize("cfg", [MINIF32, MINI64], ids=lambda c: c.name)
+def test_repeated_same_shape_steps_replay_graphs_correctly(llma, cfg):
+    """The step's launches are captured into a HIP graph the second time a shape is seen and
+    replayed afterwards.  Eight consecutive steps of the same shape (k = 4), with host work and
+    synchronisation in between, are each compared with the oracle: eager, captured and replayed
+    executions must all be right, also with graphs switched off."""
+    w = synth.make_weights(cfg, 9, gain_jitter=0.2)
+    om = OracleModel(cfg, w)
+    prompt = synth.uniform_tokens(4, 5, 21, cfg.vocab)
+    for use_graph in (1, 0):
+        ctx = llma.Context(cfg, w, max_seq=256, max_batch=1, max_k=8)
+        ctx.set_option(llma.LLMA_OPT_USE_GRAPH, use_graph)
+        ctx.enable_logits_dump(8)
+        ctx.prefill(prompt)
+        cache = om.new_cache(256)
+        om.forward(prompt[:-1], cache, 0)
+        T, pending = len(prompt) - 1, int(prompt[-1])
+        for step in range(8):
+            draft = synth.uniform_tokens(7, 100 + step, 4, cfg.vocab).tolist()
+            want = om.forward([pending] + draft, cache, T)
+            o = argmax_tokens(want)
+            a = 0
+            while a < 4 and o[a] == draft[a]:
+                a += 1
+            na, nxt, emitted = ctx.verify_step(draft)
+            assert_logits_close(ctx.logits(5), want, cfg, f"graph={use_graph} step {step}")
+            assert (na, nxt) == (a, int(o[a]))
+            T += na + 1
+            pending = nxt
+            assert ctx.get_state() == (T, pending)
+        ctx.close()
+
+
 def test_rows_bit_identical_across_row_counts(llma):
-    """Row j of a k-row step must equal, bit for bit, the same token processed in a one-row step
-    after the preceding tokens went through in any other grouping (fixed reduction orders).
+    """Row j of a k-row decoding step must equal, bit for bit, the same token processed in a
+    one-row step after the preceding tokens went through in one-row steps (fixed reduction
+    orders): that is what makes LLMA output identical to stepwise greedy output on the GPU.
     Run A: state after 251 prompt tokens, one step with 19 drafts -> logits rows 0..19.
-    Run B_j: prompt extended by j of those drafts (fed in 32-row prefill chunks), one plain step.
-    Row j of A is conditioned on exactly the same context as B_j's single row."""
+    Run B: same state, then one-row steps; after each step the pending token is overwritten with
+    the next draft (so the context follows the drafts whatever the model emits).
+    Row j of A is conditioned on exactly the same context as B's j-th step."""
     for cfg in (MINI64, MINI128, synth.TINY):
         w = synth.make_weights(cfg, 5)
         toks = synth.uniform_tokens(2, 6, 300, cfg.vocab)
         ctx = llma.Context(cfg, w, max_seq=512, max_batch=1, max_k=32)
         ctx.enable_logits_dump(33)
-        ctx.prefill(toks[:251])                          # T = 250: the step straddles the 256-key chunk edge
+        ctx.prefill(toks[:251])                          # T = 250: the step straddles the 256-position chunk edge
         ctx.verify_step(toks[251:270])
         A = ctx.logits(20).copy()
-        for j in (0, 1, 5, 6, 7, 19):
-            ctx.reset()
-            ctx.prefill(toks[:251 + j])
+        ctx.reset()
+        ctx.prefill(toks[:251])
+        for j in range(20):
             ctx.verify_step([])
             B = ctx.logits(1)
             assert np.array_equal(A[j], B[0]), (cfg.name, j, float(np.abs(A[j] - B[0]).max()))
+            if j < 19:
+                ctx.set_pending(int(toks[251 + j]))
+        # and with 33 rows (three row tiles) against two 17/16-row steps' worth of one-row steps
+        ctx.reset()
+        ctx.prefill(toks[:200])
+        ctx.verify_step(toks[200:232])
+        A = ctx.logits(33).copy()
+        ctx.reset()
+        ctx.prefill(toks[:200])
+        for j in range(33):
+            ctx.verify_step([])
+            assert np.array_equal(A[j], ctx.logits(1)[0]), (cfg.name, "33 rows", j)
+            if j < 32:
+                ctx.set_pending(int(toks[200 + j]))
         ctx.close()
 
 
