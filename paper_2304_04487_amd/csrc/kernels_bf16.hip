@@ -485,7 +485,11 @@ template <int NT, int EPI, bool SPLIT, int FT>
 __global__ __launch_bounds__(1024) void gemm_tilek_bf16(GemmArgs a) {
     constexpr int TILES = (EPI == EPI_SWIGLU) ? 2 : 1;
     constexpr int AT = FT * TILES;                 // weight tiles per k-step
-    constexpr int UB = (AT * NT >= 4) ? 1 : 2;     // k-steps per load batch
+#ifndef TK_UB_SMALL
+#define TK_UB_SMALL 2
+#define TK_UB_BIG 1
+#endif
+    constexpr int UB = (AT * NT >= 4) ? TK_UB_BIG : TK_UB_SMALL;     // k-steps per load batch
     constexpr int PL = SPLIT ? 2 : 1;
     extern __shared__ f32x4 red[];                 // [W][AT][NT][64], then rstd[16*NT] floats
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, W = blockDim.x >> 6;
