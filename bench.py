@@ -34,6 +34,19 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def measured_traffic():
+    """HBM bytes per launch of the gate/up GEMM from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE + WRITE_SIZE, calibrated on a copy of known size); None if not recorded."""
+    path = os.path.join(ROOT, "profiles", "gemm_gate_up_7b_decode_step_pmc.md")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return int(float(line.split(":")[1]))
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(wl, prompt_len: int, budget_s: float = 25.0):
     """The oracle as it stands, on a bounded sample: a model with the first 2 of the L layers plus
     the LM head (float32 copies of the weights), one-row greedy steps on top of a T = prompt_len
@@ -60,12 +73,12 @@ def cpu_baseline(wl, prompt_len: int, budget_s: float = 25.0):
         tok = int(np.argmax(lg[0]))
         t_full += time.perf_counter() - s
         n_full += 1
-        if n_full >= 3 and (time.perf_counter() - t0 > budget_s / 2 or n_full >= 24):
+        if n_full >= 3 and (time.perf_counter() - t0 > budget_s / 2 or n_full >= 256):
             break
     # head alone: a 0-layer model
     om.layers = []
     t_head, n_head = 0.0, 0
-    while n_head < 3 or (t_head < budget_s / 6 and n_head < 24):
+    while n_head < 3 or (t_head < budget_s / 6 and n_head < 256):
         s = time.perf_counter()
         om.forward([tok], cache, T)
         t_head += time.perf_counter() - s
@@ -95,6 +108,9 @@ def main():
     ap.add_argument("--k", type=int, default=None, help="copy length (default: the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="skip the k = 0 / 1 / ... comparison runs")
+    ap.add_argument("--profile-steps", type=int, default=0,
+                    help="profiling aid (for rocprofv3): skip the benchmark, run this many k-draft verification steps "
+                         "on a random KV cache of prompt length plus one plain 256 MiB device copy, print nothing")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1")
@@ -118,6 +134,25 @@ def main():
     ctx = llma.Context(cfg, w, max_seq=wl.prompt_len + wl.max_new + 64, max_batch=1, max_k=max(16, k))
     del w
     log(f"[bench] context created in {time.time() - t0:.1f}s, {ctx.device_bytes() / 1e9:.2f} GB on device")
+
+    if args.profile_steps:
+        # what one decoding step launches, in isolation, for counter collection: the cache content does
+        # not matter for traffic, so it is imported instead of computed; the copy of known size
+        # calibrates the FETCH_SIZE / WRITE_SIZE counters
+        for l in range(cfg.n_layers):
+            kk, vv = synth.make_kv_fill(cfg, wl.seed, 1, wl.prompt_len, l)
+            ctx.kv_import(0, l, torch.from_numpy(kk[0]).cuda(), torch.from_numpy(vv[0]).cuda(), wl.prompt_len)
+        ctx.set_pending(1)
+        src = torch.ones(256 * 1024 * 1024 // 4, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        drafts = synth.uniform_tokens(wl.seed, 77, k, cfg.vocab)
+        for _ in range(args.profile_steps):
+            ctx.verify_step(drafts)
+        torch.cuda.synchronize()
+        ctx.close()
+        return
 
     def timed_generate(ref, offs, n, kk, reps):
         torch.cuda.synchronize()
@@ -160,8 +195,9 @@ def main():
     gu_bytes = 2 * cfg.d_ffn * cfg.d_model * 2              # gate + up matrices, bf16, read once
     avg_ms = total_ms / max(launches, 1)
     achieved = gu_bytes / (avg_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "gemm_skinny_bf16<SWIGLU> (FFN gate/up)", "achieved": round(achieved, 1),
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+    roofline = {"bound": "hbm", "kernel": "gemm_tilek_bf16<SWIGLU> (FFN gate/up GEMM of a decoding step)",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(),
                 "avg_launch_us": round(avg_ms * 1e3, 2), "launches": launches, "bytes_per_launch": gu_bytes}
 
     # ---- whole verify step against the roofline (all weights once + KV read)
