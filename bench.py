@@ -60,7 +60,7 @@ def cpu_baseline(wl, prompt_len: int, budget_s: float = 25.0):
     om = OracleModel(cfg, w, dtype=np.float32)
     del w
     T = prompt_len
-    cache = om.new_cache(T + 64)
+    cache = om.new_cache(T + 320)
     for l in range(nl):                      # KV fill stands in for the prompt's keys/values
         cache.k[l][:, :T] = 1.0
         cache.v[l][:, :T] = 0.5
