@@ -76,13 +76,10 @@ enum { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LMHEAD = 3, EPI_QKV = 4
 // how one weight matrix is cut into work: a function of its shape only (never of the row count)
 struct GemmPlan {
     int N, K;        // logical shape (SWIGLU: N = d_ffn, the matrix has 2N rows)
-    int KSp;         // k-steps per feature tile incl. zero padding, = S * KSS
-    int S, KSS;      // K slices and k-steps per slice
-    int G;           // workgroups per slice
-    int W;           // waves per workgroup
-    int tk_ft;       // single-kernel (tile-K) variant: feature tiles per workgroup
-    int tk_waves;    //   and waves per workgroup
+    int KSp;         // k-steps (of 32) per feature tile
     int tasks;       // feature tiles (SWIGLU: gate/up tile pairs)
+    int tk_ft;       // tile-K kernel: feature tiles per workgroup
+    int tk_waves;    //   and waves per workgroup
 };
 
 struct GemmArgs {          // bf16 path (fields marked f32 are used by the fp32 kernels only)
@@ -94,12 +91,12 @@ struct GemmArgs {          // bf16 path (fields marked f32 are used by the fp32 
     int rows;              // valid rows
     int epi;
     int split;             // use Xlo
-    int tilek;             // 1: single-kernel tile-K variant (decoding steps), 0: slice-K + fix-up (prompt processing)
-    float *partial;        // [tasks][S][tiles][NT][64] f32x4 partial sums
     // inputs of the epilogues
     const float *ssq_in;   // [rows][ssq_tiles] sums of squares of the producer's residual rows
     int ssq_tiles;         //   rstd[row] = rsqrt(sum / (16 ssq_tiles) + eps)
     float eps;
+    const float *rstd_in;  // panel GEMM only: [rows] precomputed rstd (instead of ssq_in)
+    int panel_rb;          // panel GEMM only: row blocks (set by the launcher)
     // EPI_STORE (f32) / EPI_RESID / EPI_LMHEAD
     float *out;            // STORE: [rows][N]; RESID: h[rows][N] += ; LMHEAD: optional logits dump (may be null)
     // EPI_RESID: prepares the next RMSNorm'd GEMM input
@@ -129,6 +126,7 @@ struct AttnArgs {
     int n_seqs, m;          // rows per sequence
     int H, dh, max_seq;
     int n_chunks;           // launched chunks (upper bound over the batch)
+    int n_rblocks;          // row blocks per sequence (set by the launcher)
     float scale;
     float *po, *pm, *pl;    // partials
     void *out_hi, *out_lo;  // bf16: tiled planes over d_model (out_KSp k-steps per row tile); f32: out_hi = [R][d_model]

@@ -4,13 +4,14 @@
 
 // ---- bf16 path (kernels_bf16.hip)
 GemmPlan make_gemm_plan(int N, int K, int tiles_per_task);
-size_t gemm_bf16_lds_bytes(const GemmPlan &p, int nt, int split);
 void launch_pack_weight(const void *src, void *dst, int N, int K, int KSp, int rope_dh, int d, hipStream_t st);
 void launch_kv_import_bf16(const void *k, const void *v, void *kh, void *kl, void *vh, void *vl, int H, int len, int dh,
                            int max_seq, hipStream_t st);
 void launch_embed_prep_bf16(const void *embed, const int *row_tok, const float *gain, float *h, void *nx_hi, void *nx_lo,
                             float *ssq_out, int R, int d, int KSp, hipStream_t st);
 void launch_gemm_bf16(const GemmArgs &a, hipStream_t st);
+void launch_gemm_panel_bf16(const GemmArgs &a, hipStream_t st);
+void launch_rstd_rows(const float *ssq, int ssq_tiles, float eps, float *rstd, int rows, hipStream_t st);
 void launch_attn_bf16(const AttnArgs &a, hipStream_t st);
 
 // ---- fp32 path (kernels_f32.hip)

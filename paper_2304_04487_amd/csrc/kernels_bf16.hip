@@ -17,6 +17,13 @@
 #include "common.h"
 #include "kernels.h"
 
+#define PANEL_PICK_RT(a, b, c) a
+#define PANEL_PICK_FT(a, b, c) b
+#define PANEL_PICK_WV(a, b, c) c
+#define PANEL_CFG_RT(cfg) PANEL_PICK_RT(cfg)
+#define PANEL_CFG_FT(cfg) PANEL_PICK_FT(cfg)
+#define PANEL_CFG_WV(cfg) PANEL_PICK_WV(cfg)
+
 // =============================================================================================
 // weight re-tiling: row-major [N][K] bf16 -> 1 KiB MFMA A-operand blocks (see common.h)
 // =============================================================================================
@@ -134,15 +141,10 @@ void launch_embed_prep_bf16(const void *embed, const int *row_tok, const float *
 // =============================================================================================
 // skinny GEMM  Y[rows][N] = X[rows][K] . W[N][K]^T,  rows <= 16*NT
 // =============================================================================================
-// Two kernels.  The first streams the weights: the K axis is cut into S slices, a workgroup
-// belongs to one slice, copies that slice of the activations (hi and lo planes, already in
-// B-operand order) into LDS once, then each of its waves walks over feature tiles, streaming the
-// slice's KSS weight blocks of a tile straight from HBM into MFMA A operands (non-temporal,
-// 1 KiB per wave-load, next batch in flight while the current one is multiplied) and taking B
-// operands from LDS.  D[i][n] = sum_k A[i][k] B[k][n] with i = feature, n = activation row, so
-// lane l ends with features 4(l/16)..+3 of row l%16.  Each (tile, slice) partial goes to a
-// scratch buffer.  The second kernel adds the S partials of every tile in slice order and runs
-// the fused epilogue.  S, KSS and the tile walk depend on the matrix shape only.
+// Two kernels share the fused epilogues below: the tile-K kernel for decoding steps (few rows,
+// HBM-bound weight streaming) and the panel kernel for prompt processing (hundreds of rows,
+// MFMA-bound).  D[i][n] = sum_k A[i][k] B[k][n] with i = feature, n = activation row, so a lane
+// ends with features 4(l/16)..+3 of row l%16 of every row tile.
 // ---- fused epilogues.  Lane l holds features 16 task + 4 (l/16) .. +3 of row 16 t + l%16.
 // Everything an epilogue reads from memory is fetched by epi_prefetch() before the partial sums
 // are reduced, so the kernel has one memory round trip on its critical path instead of three.
@@ -287,199 +289,13 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, const GemmPlan 
     }
 }
 
-template <int NT, int TILES, bool SPLIT>
-__global__ __launch_bounds__(512) void gemm_slicek_bf16(GemmArgs a) {
-    constexpr int UH = 8 / TILES;                  // k-steps per load batch: 8 KiB in flight per wave and batch
-    constexpr int PL = SPLIT ? 2 : 1;
-    extern __shared__ u32x4 xs[];                  // [PL][NT][KSS][64]
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, W = blockDim.x >> 6;
-    const GemmPlan &p = a.plan;
-    const int S = p.S, KSS = p.KSS, KSp = p.KSp;
-    const int s = blockIdx.x % S, g = blockIdx.x / S;
-    const int ks0 = s * KSS;
-    const int NB = (KSS + UH - 1) / UH;            // load batches per (tile, slice)
-    const int stride = p.G * W;
-
-    // one batch of weight blocks of (task, batch kb): TILES x UH coalesced 1 KiB wave-loads.  A ragged
-    // last batch re-reads the slice's last block instead of running past it.
-    auto issue = [&](int task, int kb, u32x4 (&buf)[TILES][UH]) {
-#pragma unroll
-        for (int i = 0; i < TILES; ++i) {
-            const u32x4 *wp = (const u32x4 *)a.W + ((size_t)(task + i * p.tasks) * KSp + ks0) * 64 + lane;
-#pragma unroll
-            for (int u = 0; u < UH; ++u) {
-                int k = kb * UH + u;
-                k = k < KSS ? k : KSS - 1;
-                buf[i][u] = __builtin_nontemporal_load(wp + k * 64);
-            }
-        }
-    };
-    auto compute = [&](int kb, u32x4 (&buf)[TILES][UH], f32x4 (&acc)[TILES][NT]) {
-#pragma unroll
-        for (int u = 0; u < UH; ++u) {
-            const int k = kb * UH + u;
-            if (k < KSS) {
-#pragma unroll
-                for (int t = 0; t < NT; ++t) {
-                    const u32x4 bh = xs[(t * KSS + k) * 64 + lane];
-#pragma unroll
-                    for (int i = 0; i < TILES; ++i) acc[i][t] = mfma16x16x32(buf[i][u], bh, acc[i][t]);
-                    if (SPLIT) {
-                        const u32x4 bl = xs[((NT + t) * KSS + k) * 64 + lane];
-#pragma unroll
-                        for (int i = 0; i < TILES; ++i) acc[i][t] = mfma16x16x32(buf[i][u], bl, acc[i][t]);
-                    }
-                }
-            }
-        }
-    };
-    // the (tile, slice) partial of this wave: one coalesced 1 KiB store per accumulator
-    auto store_partial = [&](int task, f32x4 (&acc)[TILES][NT]) {
-        f32x4 *pp = (f32x4 *)a.partial + ((size_t)task * S + s) * (TILES * NT * 64) + lane;
-#pragma unroll
-        for (int i = 0; i < TILES; ++i)
-#pragma unroll
-            for (int t = 0; t < NT; ++t) pp[(i * NT + t) * 64] = acc[i][t];
-    };
-
-    int task = g * W + wave, kb = 0;
-    u32x4 bufA[TILES][UH], bufB[TILES][UH];
-    if (task < p.tasks) issue(task, 0, bufA);      // weights do not depend on the activations: start streaming first
-
-    // ---- activations of this slice -> LDS (all loads of a thread in flight together)
-    {
-        const int per_plane = NT * KSS * 64;       // 16-byte pieces per plane
-        for (int base = 0; base < per_plane; base += 4 * blockDim.x) {
-            u32x4 vh[4], vl[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int i = base + j * blockDim.x + threadIdx.x;
-                if (i < per_plane) {
-                    const int t = i / (KSS * 64), rem = i % (KSS * 64);
-                    const size_t src = ((size_t)t * KSp + ks0) * 64 + rem;
-                    vh[j] = ((const u32x4 *)a.Xhi)[src];
-                    if (SPLIT) vl[j] = ((const u32x4 *)a.Xlo)[src];
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int i = base + j * blockDim.x + threadIdx.x;
-                if (i < per_plane) {
-                    xs[i] = vh[j];
-                    if (SPLIT) xs[per_plane + i] = vl[j];
-                }
-            }
-        }
-    }
-    __syncthreads();
-
-    // ---- software pipeline over the wave's (tile, batch) sequence: while one batch feeds the
-    //      MFMAs the next one (of this tile or of the wave's next tile) is already in flight
-    f32x4 acc[TILES][NT];
-    while (task < p.tasks) {
-        {   // compute bufA, prefetch into bufB
-            int ntask = task, nkb = kb + 1;
-            if (nkb == NB) { nkb = 0; ntask = task + stride; }
-            if (ntask < p.tasks) issue(ntask, nkb, bufB);
-            if (kb == 0) {
-#pragma unroll
-                for (int i = 0; i < TILES; ++i)
-#pragma unroll
-                    for (int t = 0; t < NT; ++t) acc[i][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
-            }
-            compute(kb, bufA, acc);
-            if (kb == NB - 1) store_partial(task, acc);
-            task = ntask; kb = nkb;
-        }
-        if (task >= p.tasks) break;
-        {   // compute bufB, prefetch into bufA
-            int ntask = task, nkb = kb + 1;
-            if (nkb == NB) { nkb = 0; ntask = task + stride; }
-            if (ntask < p.tasks) issue(ntask, nkb, bufA);
-            if (kb == 0) {
-#pragma unroll
-                for (int i = 0; i < TILES; ++i)
-#pragma unroll
-                    for (int t = 0; t < NT; ++t) acc[i][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
-            }
-            compute(kb, bufB, acc);
-            if (kb == NB - 1) store_partial(task, acc);
-            task = ntask; kb = nkb;
-        }
-    }
-}
-
-// Second half of the GEMM: one wave per feature tile adds the tile's S slice partials in slice
-// order (a fixed order, so the sum does not depend on which workgroup finished first) and runs
-// the fused epilogue.  The kernel boundary between the two halves is the only synchronisation.
-template <int NT, int EPI>
-__global__ __launch_bounds__(256) void gemm_fixup_bf16(GemmArgs a) {
-    constexpr int TILES = (EPI == EPI_SWIGLU) ? 2 : 1;
-    __shared__ float rstd_s[16 * NT];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const GemmPlan &p = a.plan;
-    const int S = p.S;
-    const int task = blockIdx.x * 4 + wave;
-    f32x4 acc[TILES][NT];
-    EpiIn<NT> in;
-    if (task < p.tasks) epi_prefetch<NT, EPI>(a, p, task, lane, in);
-    if (task < p.tasks) {                          // partial loads first, the rstd reduction overlaps them
-        const f32x4 *pq = (const f32x4 *)a.partial + (size_t)task * S * (TILES * NT * 64) + lane;
-#pragma unroll
-        for (int i = 0; i < TILES; ++i)
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const f32x4 *q = pq + (i * NT + t) * 64;
-                f32x4 sum = (f32x4){0.f, 0.f, 0.f, 0.f};
-                for (int s0 = 0; s0 < S; s0 += 8) {                  // 8 independent loads in flight, added in slice order
-                    f32x4 v[8];
-#pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        if (s0 + j < S) v[j] = q[(size_t)(s0 + j) * (TILES * NT * 64)];
-#pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        if (s0 + j < S) sum = (s0 + j == 0) ? v[j] : sum + v[j];
-                }
-                acc[i][t] = sum;
-            }
-    }
-    // rstd of the rows from the producer's per-tile sums of squares: the 16 threads of a row each
-    // add one contiguous chunk of tiles in order, then combine by butterfly
-    if (EPI != EPI_RESID) {
-        const int row = threadIdx.x >> 4, i = threadIdx.x & 15;
-        const int chunk = (a.ssq_tiles + 15) / 16;
-        const int j0 = i * chunk, j1 = (j0 + chunk < a.ssq_tiles) ? j0 + chunk : a.ssq_tiles;
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            const int r = t * 16 + row;
-            float ss = 0.f;
-            if (r < a.rows) {
-                const float *sp = a.ssq_in + (size_t)r * a.ssq_tiles;
-                for (int j = j0; j < j1; j += 16) {                      // 16 loads in flight, added in tile order
-                    float v[16];
-#pragma unroll
-                    for (int u = 0; u < 16; ++u)
-                        if (j + u < j1) v[u] = sp[j + u];
-#pragma unroll
-                    for (int u = 0; u < 16; ++u)
-                        if (j + u < j1) ss += v[u];
-                }
-            }
-#pragma unroll
-            for (int off = 1; off < 16; off <<= 1) ss += __shfl_xor(ss, off);
-            if (i == 0) rstd_s[r] = 1.0f / sqrtf(ss / (float)(a.ssq_tiles * 16) + a.eps);
-        }
-        __syncthreads();
-    }
-    if (task < p.tasks) gemm_epilogue<NT, EPI, TILES>(a, p, task, lane, acc, rstd_s, in);
-}
-
 // ---------------------------------------------------------------------------------------------
-// Single-kernel variant ("tile-K"): one workgroup per FT consecutive feature tiles, its waves
-// split the K axis, B operands come straight from the tiled activation planes (1 KiB contiguous
-// per k-step and plane, shared through L2 by all workgroups), partial sums meet in LDS in wave
-// order and the first FT waves run the fused epilogue.  No scratch traffic and no second
-// kernel; more operand traffic per weight byte than the slice-K kernel.
+// tile-K kernel (decoding steps): one workgroup per FT consecutive feature tiles, its waves split
+// the K axis; each wave streams its weight blocks from HBM with non-temporal 1 KiB loads, the
+// next batch in flight while the current one feeds the MFMAs; B operands come straight from the
+// tiled activation planes (1 KiB contiguous per k-step and plane, shared through L2 by all
+// workgroups); the waves' partial sums meet in LDS and are added in wave order; the first FT
+// waves run the fused epilogue.  FT and the wave count depend on the matrix shape only.
 // ---------------------------------------------------------------------------------------------
 template <int NT, int EPI, bool SPLIT, int FT>
 __global__ __launch_bounds__(1024) void gemm_tilek_bf16(GemmArgs a) {
@@ -626,34 +442,16 @@ template <int NT, int EPI>
 static void launch_gemm_nt_epi(const GemmArgs &a, hipStream_t st) {
     constexpr int TILES = (EPI == EPI_SWIGLU) ? 2 : 1;
     const GemmPlan &p = a.plan;
-    if (a.tilek) {                                  // single-kernel variant (decoding steps)
-        if (TILES == 2) {
-            if (p.tk_ft == 1) launch_tilek<NT, EPI, 1>(a, st);
-            else if (p.tk_ft == 2) launch_tilek<NT, EPI, 2>(a, st);
-            else launch_tilek<NT, EPI, 3>(a, st);
-        } else {
-            if (p.tk_ft == 1) launch_tilek<NT, EPI, 1>(a, st);
-            else if (p.tk_ft == 2) launch_tilek<NT, EPI, 2>(a, st);
-            else if (p.tk_ft == 3) launch_tilek<NT, EPI, 3>(a, st);
-            else if (p.tk_ft == 4) launch_tilek<NT, EPI, 4>(a, st);
-            else if (p.tk_ft <= 6) launch_tilek<NT, EPI, 6>(a, st);
-            else launch_tilek<NT, EPI, 8>(a, st);
-        }
-        return;
-    }
-    const int planes = a.split ? 2 : 1;
-    const size_t lds = (size_t)planes * NT * p.KSS * 1024;
-    dim3 grid(p.S * p.G), block(p.W * 64);
-    if (a.split) {
-        static bool attr_done = false;
-        if (!attr_done) { (void)hipFuncSetAttribute((const void *)gemm_slicek_bf16<NT, TILES, true>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); attr_done = true; }
-        hipLaunchKernelGGL((gemm_slicek_bf16<NT, TILES, true>), grid, block, lds, st, a);
+    if (TILES == 2) {
+        if (p.tk_ft == 1) launch_tilek<NT, EPI, 1>(a, st);
+        else if (p.tk_ft == 2) launch_tilek<NT, EPI, 2>(a, st);
+        else launch_tilek<NT, EPI, 3>(a, st);
     } else {
-        static bool attr_done = false;
-        if (!attr_done) { (void)hipFuncSetAttribute((const void *)gemm_slicek_bf16<NT, TILES, false>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); attr_done = true; }
-        hipLaunchKernelGGL((gemm_slicek_bf16<NT, TILES, false>), grid, block, lds, st, a);
+        if (p.tk_ft == 1) launch_tilek<NT, EPI, 1>(a, st);
+        else if (p.tk_ft == 2) launch_tilek<NT, EPI, 2>(a, st);
+        else if (p.tk_ft == 3) launch_tilek<NT, EPI, 3>(a, st);
+        else launch_tilek<NT, EPI, 4>(a, st);
     }
-    hipLaunchKernelGGL((gemm_fixup_bf16<NT, EPI>), dim3((p.tasks + 3) / 4), dim3(256), 0, st, a);
 }
 
 template <int NT>
@@ -666,19 +464,216 @@ static void launch_gemm_nt(const GemmArgs &a, hipStream_t st) {
     }
 }
 
-// LDS bytes one workgroup needs for nt row tiles
-size_t gemm_bf16_lds_bytes(const GemmPlan &p, int nt, int split) { return (size_t)(split ? 2 : 1) * nt * p.KSS * 1024 + 256; }
+// ---------------------------------------------------------------------------------------------
+// Panel GEMM for prompt processing (hundreds of rows): a workgroup computes a block of
+// 4*FT feature tiles x RT row tiles over the whole K axis -- no K split, no partial sums.  The
+// block's activation rows are staged through LDS in chunks of KC k-steps (double-buffered,
+// straight copies because the planes are already in B-operand order) and shared by the four
+// waves; every wave streams the weight blocks of its own FT feature tiles (TILES each) from
+// global memory / L2, where the workgroups of the other row blocks find them again.  MFMA-bound
+// by design: FT*TILES*RT*2 MFMAs per k-step and wave against RT*2 LDS operand reads.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void offset_rows(GemmArgs &a, const GemmPlan &p, int r0) {
+    const int t0 = r0 / 16;
+    a.rows = a.rows - r0;
+    if (a.out) a.out += (size_t)r0 * p.N;
+    if (a.nx_hi) { a.nx_hi = (bf16_t *)a.nx_hi + (size_t)t0 * a.nx_KSp * 512; a.nx_lo = (bf16_t *)a.nx_lo + (size_t)t0 * a.nx_KSp * 512; }
+    if (a.ssq_out) a.ssq_out += (size_t)r0 * (p.N / 16);
+    if (a.act_hi) { a.act_hi = (bf16_t *)a.act_hi + (size_t)t0 * a.act_KSp * 512; a.act_lo = (bf16_t *)a.act_lo + (size_t)t0 * a.act_KSp * 512; }
+    if (a.pval) { a.pval += (size_t)r0 * a.n_part; a.pidx += (size_t)r0 * a.n_part; }
+    if (a.row_pos) { a.row_pos += r0; a.row_slot += r0; a.row_cs += (size_t)r0 * a.dh; }
+    if (a.q_hi) { a.q_hi = (bf16_t *)a.q_hi + (size_t)t0 * (a.H * a.dh / 32) * 512; a.q_lo = (bf16_t *)a.q_lo + (size_t)t0 * (a.H * a.dh / 32) * 512; }
+}
 
-// rows are processed in blocks of whole 16-row tiles: as many tiles per launch (<= 3) as the
-// activation slice leaves room for in LDS; weights are re-streamed per block
+#define PANEL_KC 2
+template <int RT, int EPI, int FT, int WV>
+__global__ __launch_bounds__(WV * 64) void gemm_panel_bf16(GemmArgs a0) {
+    constexpr int NTHR = WV * 64;
+    constexpr int TILES = (EPI == EPI_SWIGLU) ? 2 : 1;
+    constexpr int AT = FT * TILES;
+    constexpr int KC = PANEL_KC;                   // k-steps per LDS chunk
+    constexpr int CH = RT * KC * 64;               // 16-byte pieces per plane and chunk
+    constexpr int PER = (2 * CH + NTHR - 1) / NTHR; // pieces per thread and chunk (both planes)
+    extern __shared__ u32x4 xs[];                  // [2 buffers][2 planes][RT][KC][64], then rstd[16*RT]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const GemmPlan &p = a0.plan;
+    const int KSp = p.KSp;
+    // Workgroup order: the row blocks of one feature block get ids that differ by multiples of 8, i.e.
+    // they are dispatched close together and onto the same XCD, so the feature block's weights are
+    // fetched from HBM once and found in that XCD's L2 by the other row blocks.
+    const int RB = a0.panel_rb;
+    const int grp = blockIdx.x / (8 * RB), within = blockIdx.x % (8 * RB);
+    const int fb = grp * 8 + (within & 7), rb = within >> 3;
+    const int r0 = rb * (16 * RT);
+    const int rt0 = r0 / 16;
+    float *rstd_s = (float *)(xs + 2 * 2 * CH);
+    GemmArgs a = a0;
+    offset_rows(a, p, r0);
+    const int task0 = (fb * WV + wave) * FT;        // may lie past the last tile (padding feature blocks): clamped loads, no epilogue
+
+    const u32x4 *wp[AT];
+#pragma unroll
+    for (int f = 0; f < FT; ++f)
+#pragma unroll
+        for (int i = 0; i < TILES; ++i) {
+            int task = task0 + f;
+            task = task < p.tasks ? task : p.tasks - 1;
+            wp[f * TILES + i] = (const u32x4 *)a.W + ((size_t)(task + i * p.tasks) * KSp) * 64 + lane;
+        }
+    const u32x4 *xh = (const u32x4 *)a.Xhi, *xl = (const u32x4 *)a.Xlo;
+    const int n_rt_total = (a0.rows + 15) / 16;    // row tiles that exist in the planes
+
+    // activation chunk kc -> registers (both planes); pieces of row tiles past the end read tile 0
+    auto fetch_x = [&](int kc, u32x4 (&v)[PER]) {
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int i = j * NTHR + threadIdx.x;
+            if (i < 2 * CH) {
+                const int pl = i / CH, rem = i % CH;
+                const int t = rem / (KC * 64), kk = (rem / 64) % KC, ln = rem % 64;
+                int k = kc * KC + kk;
+                k = k < KSp ? k : KSp - 1;
+                const int tt = (rt0 + t < n_rt_total) ? rt0 + t : 0;
+                const size_t src = ((size_t)tt * KSp + k) * 64 + ln;
+                v[j] = pl ? xl[src] : xh[src];
+            }
+        }
+    };
+    auto stash_x = [&](int buf, u32x4 (&v)[PER]) {
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int i = j * NTHR + threadIdx.x;
+            if (i < 2 * CH) xs[buf * 2 * CH + i] = v[j];
+        }
+    };
+    auto fetch_w = [&](int kc, u32x4 (&av)[AT][KC]) {
+#pragma unroll
+        for (int u = 0; u < KC; ++u) {
+            int k = kc * KC + u;
+            k = k < KSp ? k : KSp - 1;
+#pragma unroll
+            for (int i = 0; i < AT; ++i) av[i][u] = wp[i][(size_t)k * 64];
+        }
+    };
+
+    f32x4 acc[AT][RT];
+#pragma unroll
+    for (int i = 0; i < AT; ++i)
+#pragma unroll
+        for (int t = 0; t < RT; ++t) acc[i][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    const int NC = (KSp + KC - 1) / KC;
+    u32x4 xv[PER], avA[AT][KC], avB[AT][KC];
+    fetch_x(0, xv);
+    fetch_w(0, avA);
+    if (EPI != EPI_RESID)
+        for (int r = threadIdx.x; r < 16 * RT; r += NTHR) rstd_s[r] = (r < a.rows) ? a.rstd_in[r0 + r] : 0.f;
+    stash_x(0, xv);
+    __syncthreads();
+    for (int kc = 0; kc < NC; ++kc) {
+        const int buf = kc & 1;
+        if (kc + 1 < NC) fetch_x(kc + 1, xv);
+        auto step = [&](u32x4 (&av)[AT][KC], u32x4 (&avn)[AT][KC]) {
+            if (kc + 1 < NC) fetch_w(kc + 1, avn);
+#pragma unroll
+            for (int u = 0; u < KC; ++u) {
+                if (kc * KC + u < KSp) {
+#pragma unroll
+                    for (int t = 0; t < RT; ++t) {
+                        const u32x4 bh = xs[buf * 2 * CH + (t * KC + u) * 64 + lane];
+                        const u32x4 bl = xs[buf * 2 * CH + CH + (t * KC + u) * 64 + lane];
+#pragma unroll
+                        for (int i = 0; i < AT; ++i) {
+                            acc[i][t] = mfma16x16x32(av[i][u], bh, acc[i][t]);
+                            acc[i][t] = mfma16x16x32(av[i][u], bl, acc[i][t]);
+                        }
+                    }
+                }
+            }
+        };
+        if (buf == 0) step(avA, avB); else step(avB, avA);
+        if (kc + 1 < NC) stash_x(buf ^ 1, xv);     // the other buffer was last read before the previous barrier
+        __syncthreads();
+    }
+
+    // ---- epilogues, one feature tile (pair) at a time
+#pragma unroll
+    for (int f = 0; f < FT; ++f) {
+        const int task = task0 + f;
+        if (task < p.tasks) {
+            EpiIn<RT> in;
+            epi_prefetch<RT, EPI>(a, p, task, lane, in);
+            f32x4 sum[TILES][RT];
+#pragma unroll
+            for (int i = 0; i < TILES; ++i)
+#pragma unroll
+                for (int t = 0; t < RT; ++t) sum[i][t] = acc[f * TILES + i][t];
+            gemm_epilogue<RT, EPI, TILES>(a, p, task, lane, sum, rstd_s, in);
+        }
+    }
+}
+
+// rstd[row] = rsqrt(sum of the row's per-tile sums of squares / d + eps), same summation order as
+// the decoding kernels' in-kernel version (16 threads per row, contiguous chunks, butterfly)
+__global__ __launch_bounds__(256) void rstd_rows_kernel(const float *__restrict__ ssq, int ssq_tiles, float eps, float *__restrict__ rstd, int rows) {
+    const int r = blockIdx.x * 16 + (threadIdx.x >> 4), i = threadIdx.x & 15;
+    const int chunk = (ssq_tiles + 15) / 16;
+    const int j0 = i * chunk, j1 = (j0 + chunk < ssq_tiles) ? j0 + chunk : ssq_tiles;
+    float ss = 0.f;
+    if (r < rows) {
+        const float *sp = ssq + (size_t)r * ssq_tiles;
+        for (int j = j0; j < j1; j += 16) {
+            float v[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u)
+                if (j + u < j1) v[u] = sp[j + u];
+#pragma unroll
+            for (int u = 0; u < 16; ++u)
+                if (j + u < j1) ss += v[u];
+        }
+    }
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) ss += __shfl_xor(ss, off);
+    if (i == 0 && r < rows) rstd[r] = 1.0f / sqrtf(ss / (float)(ssq_tiles * 16) + eps);
+}
+void launch_rstd_rows(const float *ssq, int ssq_tiles, float eps, float *rstd, int rows, hipStream_t st) {
+    hipLaunchKernelGGL(rstd_rows_kernel, dim3((rows + 15) / 16), dim3(256), 0, st, ssq, ssq_tiles, eps, rstd, rows);
+}
+
+template <int RT, int EPI, int FT, int WV>
+static void launch_panel_cfg(const GemmArgs &a, hipStream_t st) {
+    const GemmPlan &p = a.plan;
+    const size_t lds = (size_t)2 * 2 * RT * PANEL_KC * 1024 + 16 * RT * sizeof(float);
+    const int FB = ((p.tasks + WV * FT - 1) / (WV * FT) + 7) / 8 * 8;    // feature blocks, padded to whole groups of 8
+    GemmArgs a2 = a;
+    a2.panel_rb = (a.rows + 16 * RT - 1) / (16 * RT);
+    dim3 grid(FB * a2.panel_rb), block(WV * 64);
+    static bool attr_done = false;
+    if (!attr_done) { (void)hipFuncSetAttribute((const void *)gemm_panel_bf16<RT, EPI, FT, WV>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); attr_done = true; }
+    hipLaunchKernelGGL((gemm_panel_bf16<RT, EPI, FT, WV>), grid, block, lds, st, a2);
+}
+
+// prompt-processing GEMM over any number of rows (needs a.rstd_in for the norm-scaled epilogues)
+#ifndef PANEL_CFG
+#define PANEL_CFG 8, 2, 8      /* row tiles, weight tiles per wave, waves */
+#define PANEL_CFG_GU 8, 1, 8
+#endif
+void launch_gemm_panel_bf16(const GemmArgs &a, hipStream_t st) {
+    switch (a.epi) {
+        case EPI_RESID: launch_panel_cfg<PANEL_CFG_RT(PANEL_CFG), EPI_RESID, PANEL_CFG_FT(PANEL_CFG), PANEL_CFG_WV(PANEL_CFG)>(a, st); break;
+        case EPI_SWIGLU: launch_panel_cfg<PANEL_CFG_RT(PANEL_CFG_GU), EPI_SWIGLU, PANEL_CFG_FT(PANEL_CFG_GU), PANEL_CFG_WV(PANEL_CFG_GU)>(a, st); break;
+        case EPI_QKV: launch_panel_cfg<PANEL_CFG_RT(PANEL_CFG), EPI_QKV, PANEL_CFG_FT(PANEL_CFG), PANEL_CFG_WV(PANEL_CFG)>(a, st); break;
+        default: launch_panel_cfg<PANEL_CFG_RT(PANEL_CFG), EPI_LMHEAD, PANEL_CFG_FT(PANEL_CFG), PANEL_CFG_WV(PANEL_CFG)>(a, st); break;
+    }
+}
+
+// decoding-step GEMM: up to 48 rows (three row tiles) per launch; more rows (batched steps) are
+// processed in blocks of 48, re-streaming the weights per block
 void launch_gemm_bf16(const GemmArgs &a0, hipStream_t st) {
     const GemmPlan &p = a0.plan;
-    int nt_max = 3;
-    while (nt_max > 1 && gemm_bf16_lds_bytes(p, nt_max, a0.split) > 150 * 1024) --nt_max;
-    const int block_rows = nt_max * 16;
-    for (int r0 = 0; r0 < a0.rows; r0 += block_rows) {
+    for (int r0 = 0; r0 < a0.rows; r0 += 48) {
         GemmArgs a = a0;
-        const int rows = a0.rows - r0 < block_rows ? a0.rows - r0 : block_rows;
+        const int rows = a0.rows - r0 < 48 ? a0.rows - r0 : 48;
         const int t0 = r0 / 16;
         a.rows = rows;
         a.Xhi = (const bf16_t *)a0.Xhi + (size_t)t0 * p.KSp * 512;
@@ -697,44 +692,17 @@ void launch_gemm_bf16(const GemmArgs &a0, hipStream_t st) {
     }
 }
 
-// waves per GEMM workgroup (LLMA_GEMM_W overrides, for experiments)
-static int gemm_wg_waves() {
-    const char *e = getenv("LLMA_GEMM_W");
-    int w = e ? atoi(e) : 8;
-    return (w == 4 || w == 8) ? w : 8;
-}
-
-// how a [N][K] matrix is cut: slices of ~16 k-steps (padding K up if needed), ~2048-4096 waves
+// how a [N][K] weight matrix is cut into work for the tile-K kernel: tiles per workgroup so that the
+// grid is about one to three workgroups per compute unit, 16 waves when a workgroup owns several
+// tiles, else 8 (measured best on the 7B shapes; LLMA_GEMM_TK / LLMA_GEMM_TKW override for experiments)
 GemmPlan make_gemm_plan(int N, int K, int tiles_per_task) {
     GemmPlan p;
     p.N = N; p.K = K;
-    const int KS = K / 32;
-    int best_kss = 16, best_pad = 1 << 30;
-    if (KS <= 24) { best_kss = KS; best_pad = 0; }
-    else if (KS % 16 == 0) { best_kss = 16; best_pad = 0; }
-    else
-        for (int kss = 24; kss >= 12; --kss) {
-            const int s = (KS + kss - 1) / kss, pad = s * kss - KS;
-            if (pad < best_pad) { best_pad = pad; best_kss = kss; }
-        }
-    p.KSS = best_kss;
-    p.S = (KS + best_kss - 1) / best_kss;
-    p.KSp = p.S * p.KSS;
+    p.KSp = K / 32;
     p.tasks = N / 16;
-    // tiles per wave so that S * G * 4 waves is about 2048..4096
-    int waves_per_slice = 3072 / p.S;
-    if (waves_per_slice < 4) waves_per_slice = 4;
-    int tpw = (p.tasks + waves_per_slice - 1) / waves_per_slice;
-    if (tpw < 1) tpw = 1;
-    if (tiles_per_task == 2 && tpw > 2) tpw = (tpw + 1) / 2;
-    // single-kernel variant: tiles per workgroup so that the grid is about one or two workgroups
-    // per compute unit, 16 waves when a workgroup owns several tiles, else 8
     p.tk_ft = (tiles_per_task == 2) ? 1 : (p.tasks >= 1536 ? 4 : (p.tasks >= 640 ? 3 : 1));
     p.tk_waves = p.tk_ft > 1 ? 16 : 8;
     { const char *e = getenv("LLMA_GEMM_TK"); if (e) p.tk_ft = atoi(e); const char *w = getenv("LLMA_GEMM_TKW"); if (w) p.tk_waves = atoi(w); }
-    p.W = gemm_wg_waves();
-    if (tpw > 1 && p.W > 4 && p.tasks < 4 * p.W * 64 / p.S) p.W = 4;
-    p.G = (p.tasks + p.W * tpw - 1) / (p.W * tpw);
     return p;
 }
 
@@ -756,11 +724,13 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
     __shared__ float sm[4][RQ], sl[4][RQ];
     __shared__ float so[4][RQ][DH + 4];
 
-    const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z / a.n_rblocks, rb = blockIdx.z % a.n_rblocks;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 15, g = lane >> 4;
     const int slot = a.slot_const >= 0 ? a.slot_const : a.batch_slots[b];
     const int m = a.m;
+    const int j0 = rb * RQ;                             // first row of this row block
+    const int m_blk = (m - j0 < RQ) ? m - j0 : RQ;      // rows of this block
     const int chunk0 = c * ATTN_CHUNK;
     const int d_model = a.H * DH;
     const int key0 = chunk0 + wave * 32;
@@ -787,7 +757,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
         }
     }
     const int T = a.T[slot];
-    const int kv_len = T + m;
+    const int kv_len = T + j0 + m_blk;                  // positions the block's last row can see
     if (chunk0 >= kv_len) return;                       // uniform for the workgroup
     const bool active = key0 < kv_len;                  // uniform for the wave
 
@@ -804,7 +774,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
     if (active) {
 #pragma unroll
         for (int q = 0; q < NTQ; ++q) {
-            const int j = q * 16 + n;
+            const int j = j0 + q * 16 + n;
             const bool valid = j < m;
             const int rpos = valid ? T + j : -1;
             const int r = b * m + (valid ? j : 0);
@@ -872,8 +842,8 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
         for (int dt = 0; dt < DT; ++dt) *(f32x4 *)&so[wave][q * 16 + n][dt * 16 + 4 * g] = o[q][dt];
     }
     __syncthreads();
-    const size_t pbase = (((size_t)b * a.H + h) * a.n_chunks + c) * RQ;
-    for (int idx = threadIdx.x; idx < m * (DH / 4); idx += 256) {
+    const size_t pbase = (((size_t)b * a.H + h) * a.n_chunks + c) * ((size_t)a.n_rblocks * RQ) + j0;
+    for (int idx = threadIdx.x; idx < m_blk * (DH / 4); idx += 256) {
         const int j = idx / (DH / 4), d4 = idx % (DH / 4);
         float M = LLMA_NEG_INF;
 #pragma unroll
@@ -887,7 +857,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
         }
         *(f32x4 *)(a.po + (pbase + j) * DH + d4 * 4) = acc;
     }
-    if (threadIdx.x < m) {
+    if (threadIdx.x < m_blk) {
         int j = threadIdx.x;
         float M = LLMA_NEG_INF;
         for (int w = 0; w < 4; ++w) M = fmaxf(M, sm[w][j]);
@@ -950,13 +920,16 @@ __global__ void attn_combine_bf16_kernel(AttnArgs a, int rq) {
 }
 
 template <int DH, bool KVS>
-static void launch_attn_dh(const AttnArgs &a, hipStream_t st) {
-    const int ntq = (a.m + 15) / 16;
-    dim3 grid(a.n_chunks, a.H, a.n_seqs);
+static void launch_attn_dh(const AttnArgs &a0, hipStream_t st) {
+    // up to 48 rows per workgroup; longer row lists (prompt processing) are cut into row blocks
+    AttnArgs a = a0;
+    const int ntq = a.m > 32 ? 3 : (a.m + 15) / 16;
+    a.n_rblocks = (a.m + ntq * 16 - 1) / (ntq * 16);
+    dim3 grid(a.n_chunks, a.H, a.n_seqs * a.n_rblocks);
     if (ntq == 1) hipLaunchKernelGGL((attn_bf16_kernel<DH, 1, KVS>), grid, dim3(256), 0, st, a);
     else if (ntq == 2) hipLaunchKernelGGL((attn_bf16_kernel<DH, 2, KVS>), grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL((attn_bf16_kernel<DH, 3, KVS>), grid, dim3(256), 0, st, a);
-    hipLaunchKernelGGL((attn_combine_bf16_kernel<DH>), dim3(a.n_seqs * a.m, a.H), dim3(DH / 4), 0, st, a, ntq * 16);
+    hipLaunchKernelGGL((attn_combine_bf16_kernel<DH>), dim3(a.n_seqs * a.m, a.H), dim3(DH / 4), 0, st, a, a.n_rblocks * ntq * 16);
 }
 
 void launch_attn_bf16(const AttnArgs &a, hipStream_t st) {

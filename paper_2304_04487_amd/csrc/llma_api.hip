@@ -19,7 +19,8 @@
 
 static thread_local std::string g_err;      // errors of calls that have no context
 
-#define PREFILL_ROWS 48
+#define PREFILL_ROWS_F32 48      // fp32 path: prompt rows per pass
+#define PREFILL_ROWS_MAX 2048    // bf16 path: prompt rows per pass (whole prompt when it fits)
 
 struct EventPair { hipEvent_t a, b; };
 
@@ -56,9 +57,10 @@ struct llma_ctx {
     void *xhi = nullptr, *xlo = nullptr, *q = nullptr, *q_lo = nullptr, *att_hi = nullptr, *att_lo = nullptr, *act_hi = nullptr, *act_lo = nullptr;
     float *po = nullptr, *pm = nullptr, *pl = nullptr;
     int nc_max = 0;
-    // bf16 GEMM work division, partial-sum scratch, per-tile sums of squares
+    // bf16 GEMM work division, per-tile sums of squares of the residual rows, rstd of prompt rows
     GemmPlan plan_qkv{}, plan_o{}, plan_gu{}, plan_down{}, plan_lm{};
-    float *partial = nullptr, *ssq = nullptr;
+    float *ssq = nullptr, *rstd = nullptr;
+    int Pmax = 0;                      // prompt rows processed per pass
     float *pval = nullptr;
     int *pidx = nullptr;
     int n_part = 0;
@@ -163,9 +165,6 @@ static int create_impl(llma_ctx *c, const llma_weights *w) {
         c->plan_gu = make_gemm_plan(F, d, 2);
         c->plan_down = make_gemm_plan(d, F, 1);
         c->plan_lm = make_gemm_plan(V, d, 1);
-        const GemmPlan *pl[] = {&c->plan_qkv, &c->plan_o, &c->plan_gu, &c->plan_down, &c->plan_lm};
-        for (const GemmPlan *p : pl)
-            if (gemm_bf16_lds_bytes(*p, 1, 1) > 150 * 1024) return fail(c, LLMA_E_INVAL, "matrix [%d x %d] does not fit the GEMM's LDS slice", p->N, p->K);
     }
     // ---- weights
     ALLOC(c, c->embed, (size_t)V * d * es);
@@ -222,8 +221,9 @@ static int create_impl(llma_ctx *c, const llma_weights *w) {
     // ---- scratch
     const int m_max = g.max_k + 1;
     c->Rmax = g.max_batch * m_max;
-    if (c->Rmax < PREFILL_ROWS) c->Rmax = PREFILL_ROWS;
-    const size_t Rp = ((size_t)c->Rmax + 15) / 16 * 16 + 48;     // slack: the GEMM reads whole 16-row tiles
+    c->Pmax = c->bf16 ? (g.max_seq < PREFILL_ROWS_MAX ? g.max_seq : PREFILL_ROWS_MAX) : PREFILL_ROWS_F32;
+    if (c->Rmax < c->Pmax) c->Rmax = c->Pmax;
+    const size_t Rp = ((size_t)c->Rmax + 127) / 128 * 128 + 48;  // slack: the GEMMs read whole row tiles / row blocks
     std::vector<std::pair<void *, size_t>> zero;
     auto zalloc = [&](void **p, size_t bytes) -> int { int r = dev_alloc(c, p, bytes); if (r == LLMA_OK) zero.push_back({*p, bytes}); return r; };
     if ((rc = zalloc((void **)&c->h, Rp * d * 4))) return rc;
@@ -235,15 +235,13 @@ static int create_impl(llma_ctx *c, const llma_weights *w) {
             (rc = zalloc(&c->act_hi, act_bytes)) || (rc = zalloc(&c->act_lo, act_bytes)))
             return rc;
         if ((rc = zalloc((void **)&c->ssq, Rp * (d / 16) * 4))) return rc;
-        size_t part = 0;
-        const GemmPlan *pl[] = {&c->plan_qkv, &c->plan_o, &c->plan_gu, &c->plan_down, &c->plan_lm};
-        for (const GemmPlan *p : pl) {
-            const size_t b = (size_t)p->tasks * p->S * (p == &c->plan_gu ? 2 : 1) * 3 * 1024;
-            if (b > part) part = b;
-        }
-        ALLOC(c, c->partial, part);
+        if ((rc = zalloc((void **)&c->rstd, Rp * 4))) return rc;
         c->nc_max = c->seq_cap / ATTN_CHUNK;
-        const size_t np = (size_t)g.max_batch * H * c->nc_max * 48;
+        // attention partials: [sequences][heads][chunks][rows]: 48 rows per sequence in decoding steps,
+        // the whole prompt pass (one sequence) in prompt processing
+        size_t np = (size_t)g.max_batch * H * c->nc_max * 48;
+        const size_t np_prompt = (size_t)H * c->nc_max * (((size_t)c->Pmax + 47) / 48 * 48);
+        if (np_prompt > np) np = np_prompt;
         ALLOC(c, c->po, np * dh * 4);
         ALLOC(c, c->pm, np * 4);
         ALLOC(c, c->pl, np * 4);
@@ -254,8 +252,9 @@ static int create_impl(llma_ctx *c, const llma_weights *w) {
     }
     for (auto &z : zero) HIP_TRY(c, hipMemsetAsync(z.first, 0, z.second, c->st));
     c->n_part = c->bf16 ? V / 16 : V;
-    ALLOC(c, c->pval, (size_t)c->Rmax * c->n_part * 4);
-    ALLOC(c, c->pidx, (size_t)c->Rmax * c->n_part * 4);
+    const size_t lm_rows = (size_t)g.max_batch * m_max;      // only decoding steps run the LM head
+    ALLOC(c, c->pval, lm_rows * c->n_part * 4);
+    ALLOC(c, c->pidx, lm_rows * c->n_part * 4);
     // ---- step state
     StepState &s = c->s;
     ALLOC(c, s.row_tok, Rp * 4);
@@ -376,8 +375,9 @@ static int forward_bf16(llma_ctx *c, int n_seqs, int m, int n_chunks, bool lm_he
     const int ksp_d = c->plan_qkv.KSp;          // k-steps per row tile of every activation plane that feeds a K = d GEMM
     launch_embed_prep_bf16(c->embed, c->s.row_tok, c->n1[0], c->h, c->xhi, c->xlo, c->ssq, R, d, ksp_d, st);
     GemmArgs base{};
-    base.rows = R; base.split = c->opt_split; base.partial = c->partial; base.eps = g.rms_eps;
-    base.tilek = lm_head ? 1 : 0;               // prompt chunks (no LM head) use the LDS-staged two-kernel variant
+    base.rows = R; base.split = c->opt_split; base.eps = g.rms_eps;
+    const bool panel = !lm_head;                // prompt passes (no LM head) use the panel GEMM
+    base.rstd_in = c->rstd;
     base.ssq_tiles = d / 16; base.H = H; base.dh = dh; base.max_seq = c->seq_cap; base.nx_KSp = ksp_d;
     AttnArgs aa{};
     aa.Qhi = c->q; aa.Qlo = c->q_lo; aa.T = c->s.T; aa.batch_slots = c->s.batch_slots; aa.slot_const = n_seqs == 1 ? slot : -1; aa.n_seqs = n_seqs; aa.m = m; aa.H = H; aa.dh = dh;
@@ -388,17 +388,21 @@ static int forward_bf16(llma_ctx *c, int n_seqs, int m, int n_chunks, bool lm_he
         ga.W = c->wqkv[l]; ga.plan = c->plan_qkv; ga.Xhi = c->xhi; ga.Xlo = c->xlo; ga.epi = EPI_QKV; ga.ssq_in = c->ssq;
         ga.row_pos = c->s.row_pos; ga.row_slot = c->s.row_slot; ga.row_cs = c->s.row_cs; ga.q_hi = c->q; ga.q_lo = c->q_lo;
         ga.k_hi = c->kc[l]; ga.k_lo = c->kc_lo[l]; ga.v_hi = c->vc[l]; ga.v_lo = c->vc_lo[l];
-        launch_gemm_bf16(ga, st);
+        if (panel) { launch_rstd_rows(c->ssq, d / 16, g.rms_eps, c->rstd, R, st); launch_gemm_panel_bf16(ga, st); }
+        else launch_gemm_bf16(ga, st);
         aa.Khi = c->kc[l]; aa.Klo = c->kc_lo[l]; aa.Vhi = c->vc[l]; aa.Vlo = c->vc_lo[l];
         launch_attn_bf16(aa, st);
         ga = base;
         ga.W = c->wo[l]; ga.plan = c->plan_o; ga.Xhi = c->att_hi; ga.Xlo = c->att_lo; ga.epi = EPI_RESID; ga.out = c->h;
         ga.gain = c->n2[l]; ga.nx_hi = c->xhi; ga.nx_lo = c->xlo; ga.ssq_out = c->ssq;
-        launch_gemm_bf16(ga, st);
+        panel ? launch_gemm_panel_bf16(ga, st) : launch_gemm_bf16(ga, st);
         ga = base;
         ga.W = c->wgu[l]; ga.plan = c->plan_gu; ga.Xhi = c->xhi; ga.Xlo = c->xlo; ga.epi = EPI_SWIGLU; ga.ssq_in = c->ssq;
         ga.act_hi = c->act_hi; ga.act_lo = c->act_lo; ga.act_KSp = c->plan_down.KSp;
-        if (c->opt_timing && lm_head) {   // decoding steps only, not prompt processing
+        if (panel) {
+            launch_rstd_rows(c->ssq, d / 16, g.rms_eps, c->rstd, R, st);
+            launch_gemm_panel_bf16(ga, st);
+        } else if (c->opt_timing) {
             EventPair ep;
             HIP_TRY(c, hipEventCreate(&ep.a));
             HIP_TRY(c, hipEventCreate(&ep.b));
@@ -412,7 +416,7 @@ static int forward_bf16(llma_ctx *c, int n_seqs, int m, int n_chunks, bool lm_he
         ga = base;
         ga.W = c->wd[l]; ga.plan = c->plan_down; ga.Xhi = c->act_hi; ga.Xlo = c->act_lo; ga.epi = EPI_RESID; ga.out = c->h;
         ga.gain = (l + 1 < L) ? c->n1[l + 1] : c->final_norm; ga.nx_hi = c->xhi; ga.nx_lo = c->xlo; ga.ssq_out = c->ssq;
-        launch_gemm_bf16(ga, st);
+        panel ? launch_gemm_panel_bf16(ga, st) : launch_gemm_bf16(ga, st);
     }
     if (lm_head) {
         GemmArgs ga = base;
@@ -563,8 +567,8 @@ static int prefill_rows(llma_ctx *c, int seq, int n_feed) {
     // the chunk's tokens are gen_prompt[T - base ..]: base = T at the start of the prompt
     HIP_TRY(c, hipMemcpyAsync(c->gen_counters + 4, &c->T_host[seq], 4, hipMemcpyHostToDevice, c->st));
     HIP_TRY(c, hipStreamSynchronize(c->st));
-    for (int off = 0; off < n_feed; off += PREFILL_ROWS) {
-        const int m = n_feed - off < PREFILL_ROWS ? n_feed - off : PREFILL_ROWS;
+    for (int off = 0; off < n_feed; off += c->Pmax) {
+        const int m = n_feed - off < c->Pmax ? n_feed - off : c->Pmax;
         int rc = run_step(c, STEP_PREFILL, 1, m, c->T_host[seq], seq);
         if (rc) return rc;
         c->T_host[seq] += m;
