@@ -700,7 +700,8 @@ GemmPlan make_gemm_plan(int N, int K, int tiles_per_task) {
     p.N = N; p.K = K;
     p.KSp = K / 32;
     p.tasks = N / 16;
-    p.tk_ft = (tiles_per_task == 2) ? 1 : (p.tasks >= 1536 ? 4 : (p.tasks >= 640 ? 3 : 1));
+    // (waves x tiles per workgroup <= 48 keeps the wave-order reduction of three row tiles inside LDS)
+    p.tk_ft = (tiles_per_task == 2) ? 1 : (p.tasks >= 640 ? 3 : 1);
     p.tk_waves = p.tk_ft > 1 ? 16 : 8;
     { const char *e = getenv("LLMA_GEMM_TK"); if (e) p.tk_ft = atoi(e); const char *w = getenv("LLMA_GEMM_TKW"); if (w) p.tk_waves = atoi(w); }
     return p;

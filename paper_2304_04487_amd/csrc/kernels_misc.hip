@@ -121,6 +121,7 @@ __global__ __launch_bounds__(256) void argmax_accept_kernel(const float *__restr
     __shared__ int wi[4];
     __shared__ int o[40];
     const int b = blockIdx.x;
+    if (gen != nullptr && *gen->n_out >= gen->max_new) return;   // a step enqueued past the end: leave all state alone
     const int keff = s.keff[b];
     for (int j = 0; j <= keff; ++j) {
         const size_t r = (size_t)b * m + j;

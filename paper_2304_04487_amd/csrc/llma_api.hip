@@ -34,6 +34,8 @@ struct llma_ctx {
     hipStream_t run_st = nullptr;      // where the launchers enqueue: st, or cap_st while capturing
     hipStream_t cap_st = nullptr;      // private stream used only to capture step graphs
     std::map<uint64_t, GraphSlot> graphs;
+    int *pin_counts = nullptr;         // pinned host ints the decoding loop's output counts are copied into
+    hipEvent_t cnt_ev[2] = {nullptr, nullptr};
     bool bf16 = false;
     std::vector<void *> allocs;
     int64_t dev_bytes = 0;
@@ -282,6 +284,9 @@ static int create_impl(llma_ctx *c, const llma_weights *w) {
     c->pending_host.assign(g.max_batch, -1);
     c->import_mask_layers.assign(g.max_batch, 0);
     HIP_TRY(c, hipStreamCreateWithFlags(&c->cap_st, hipStreamNonBlocking));
+    HIP_TRY(c, hipHostMalloc((void **)&c->pin_counts, 4 * sizeof(int), hipHostMallocDefault));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->cnt_ev[0], hipEventDisableTiming));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->cnt_ev[1], hipEventDisableTiming));
     HIP_TRY(c, hipStreamSynchronize(c->st));
     HIP_TRY(c, hipGetLastError());
     return LLMA_OK;
@@ -317,6 +322,8 @@ extern "C" int llma_destroy(llma_ctx *c) {
     (void)hipStreamSynchronize(c->st);
     for (auto &g : c->graphs) if (g.second.exec) (void)hipGraphExecDestroy(g.second.exec);
     if (c->cap_st) (void)hipStreamDestroy(c->cap_st);
+    if (c->pin_counts) (void)hipHostFree(c->pin_counts);
+    for (int i = 0; i < 2; ++i) if (c->cnt_ev[i]) (void)hipEventDestroy(c->cnt_ev[i]);
     for (auto &e : c->events) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
     for (void *p : c->allocs) (void)hipFree(p);
     delete c;
@@ -376,7 +383,10 @@ static int forward_bf16(llma_ctx *c, int n_seqs, int m, int n_chunks, bool lm_he
     launch_embed_prep_bf16(c->embed, c->s.row_tok, c->n1[0], c->h, c->xhi, c->xlo, c->ssq, R, d, ksp_d, st);
     GemmArgs base{};
     base.rows = R; base.split = c->opt_split; base.eps = g.rms_eps;
-    const bool panel = !lm_head;                // prompt passes (no LM head) use the panel GEMM
+    // prompt passes (no LM head) and batched steps with more than 256 rows use the panel GEMM (weights
+    // streamed once for all rows, MFMA-bound, needs a few hundred rows to fill the chip); other steps
+    // the tile-K GEMM, in blocks of 48 rows
+    const bool panel = !lm_head || R > 256;
     base.rstd_in = c->rstd;
     base.ssq_tiles = d / 16; base.H = H; base.dh = dh; base.max_seq = c->seq_cap; base.nx_KSp = ksp_d;
     AttnArgs aa{};
@@ -422,7 +432,8 @@ static int forward_bf16(llma_ctx *c, int n_seqs, int m, int n_chunks, bool lm_he
         GemmArgs ga = base;
         ga.W = c->lm_head; ga.plan = c->plan_lm; ga.Xhi = c->xhi; ga.Xlo = c->xlo; ga.epi = EPI_LMHEAD; ga.ssq_in = c->ssq;
         ga.out = c->logits_dump; ga.pval = c->pval; ga.pidx = c->pidx; ga.n_part = c->n_part;
-        launch_gemm_bf16(ga, st);
+        if (panel) { launch_rstd_rows(c->ssq, d / 16, g.rms_eps, c->rstd, R, st); launch_gemm_panel_bf16(ga, st); }
+        else launch_gemm_bf16(ga, st);
     }
     HIP_TRY(c, hipGetLastError());
     return LLMA_OK;
@@ -757,21 +768,36 @@ extern "C" int llma_generate(llma_ctx *c, int32_t seq, const int32_t *prompt, in
     if ((rc = push_state(c, seq))) return rc;
     if ((rc = prefill_rows(c, seq, prompt_len - 1))) return rc;
 
-    // ---- the decoding loop: trigger -> rows -> forward -> accept, all on the device; the host
-    //      only reads the output count back to know when to stop
+    // ---- the decoding loop: trigger -> rows -> forward -> accept, all on the device.  The host only
+    //      reads the output count back to know when to stop, and it does so one step late: step s+1
+    //      is already enqueued when the count of step s is awaited, so the GPU never waits for the
+    //      host.  The one step that may run after the last token is a no-op on the device (the
+    //      trigger copies nothing and the accept kernel leaves all state alone once max_new is reached).
     const int m = k + 1;
     HIP_TRY(c, hipMemcpyAsync(c->s.batch_slots, &seq, 4, hipMemcpyHostToDevice, st));
-    int produced = 0, steps = 0;
-    while (produced < max_new) {
-        if ((rc = run_step(c, STEP_GEN, 1, m, c->T_host[seq], seq))) return rc;
-        int now = 0;
-        HIP_TRY(c, hipMemcpyAsync(&now, G.n_out, 4, hipMemcpyDeviceToHost, st));
-        HIP_TRY(c, hipStreamSynchronize(st));
+    const int T0 = c->T_host[seq];
+    int produced = 0, steps = 0, enq = 0;
+    auto enqueue = [&]() -> int {
+        // cache length bound for the attention grid: every enqueued step adds at most m positions
+        int r = run_step(c, STEP_GEN, 1, m, T0 + produced + 2 * m, seq);
+        if (r) return r;
+        HIP_TRY(c, hipMemcpyAsync(c->pin_counts + (enq & 1), G.n_out, 4, hipMemcpyDeviceToHost, st));
+        HIP_TRY(c, hipEventRecord(c->cnt_ev[enq & 1], st));
+        ++enq;
+        return LLMA_OK;
+    };
+    if ((rc = enqueue())) return rc;
+    while (true) {
+        if ((rc = enqueue())) return rc;                        // one step ahead
+        HIP_TRY(c, hipEventSynchronize(c->cnt_ev[steps & 1]));
+        const int now = c->pin_counts[steps & 1];
         if (now <= produced || now > max_new) return fail(c, LLMA_E_HIP, "llma_generate: device output count went %d -> %d", produced, now);
-        c->T_host[seq] += now - produced;
         produced = now;
         ++steps;
+        if (produced >= max_new) break;
     }
+    HIP_TRY(c, hipStreamSynchronize(st));                       // drains the step that ran ahead
+    c->T_host[seq] = T0 + produced;
     HIP_TRY(c, hipMemcpyAsync(out_tokens, c->gen_y, (size_t)max_new * 4, hipMemcpyDeviceToHost, st));
     if (trace) HIP_TRY(c, hipMemcpyAsync(trace, c->gen_trace, (size_t)steps * sizeof(llma_step_rec), hipMemcpyDeviceToHost, st));
     HIP_TRY(c, hipMemcpyAsync(&c->pending_host[seq], c->s.pending + seq, 4, hipMemcpyDeviceToHost, st));

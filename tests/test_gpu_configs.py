@@ -215,3 +215,96 @@ def test_batched_verify_step_on_imported_caches(llma, kv_split):
             assert na[b] == (k if mode == "accept" else 0)
             assert ctx.get_state(slots[b]) == (T_before[b] + na[b] + 1, accs[b][1])
     ctx.close()
+
+
+# --------------------------------------------------------------------------- the verify-step microbenchmark at full size
+@pytest.mark.timeout(900)
+def test_verify_microbench_full_size(llma):
+    """BASELINE configs[4] at its real size: LLaMA-7B shape, 16 sequences, 4096-position random KV
+    caches (N(0,1) rounded to bf16; the cache keeps hi + lo planes like everywhere else, because the
+    step's own new rows need them to stay inside the logit tolerance at 32 layers), one
+    verification step for all sequences.  Two sampled sequences are checked against the oracle
+    (logits of all rows, accepted count, next token) for all-accept and all-reject drafts at k = 8;
+    then the step is timed for k in {1, 2, 4, 8, 16, 32} (all-reject drafts) and the table printed."""
+    import time
+    cfg = synth.LLAMA_7B
+    B, T, seed = 16, 4096, 4242
+    w = synth.make_weights(cfg, seed)
+    ctx = llma.Context(cfg, w, max_seq=T + 192, max_batch=B, max_k=32, kv_split=True)
+    om = OracleModel(cfg, w, dtype=np.float32)
+    del w
+    sampled = [3, 12]
+    caches = {b: om.new_cache(T + 32) for b in sampled}
+    for b in range(B):
+        for l in range(cfg.n_layers):
+            kk, vv = synth.make_kv_fill(cfg, seed + b, 1, T, l)
+            ctx.kv_import(b, l, torch.from_numpy(kk[0]).cuda(), torch.from_numpy(vv[0]).cuda(), T)
+            if b in caches:
+                caches[b].k[l][:, :T] = synth.bf16_to_f32(kk[0])
+                caches[b].v[l][:, :T] = synth.bf16_to_f32(vv[0])
+        ctx.set_pending(100 + b, b)
+    torch.cuda.synchronize()
+    k = 8
+    ctx.enable_logits_dump(B * (k + 1))
+    # all-reject: first draft differs from o_0 (checked below), others uniform
+    drafts = synth.uniform_tokens(seed, 5, B * k, cfg.vocab).reshape(B, k)
+    na, nxt, em = ctx.verify_step_batch(list(range(B)), drafts)
+    got = ctx.logits(B * (k + 1)).reshape(B, k + 1, cfg.vocab)
+    accept_drafts = {}
+    for b in sampled:
+        want = om.forward([100 + b] + drafts[b].tolist(), caches[b], T).astype(np.float64)
+        err = check_logits(got[b], want, f"microbench seq {b}")
+        o = argmax_tokens(want)
+        a = 0
+        while a < k and o[a] == drafts[b][a]:
+            a += 1
+        if top2_gap(want[a]) > ATOL + RTOL * abs(float(want[a].max())):
+            assert (int(na[b]), int(nxt[b])) == (a, int(o[a]))
+        assert ctx.get_state(b) == (T + na[b] + 1, int(nxt[b]))
+        print(f"  seq {b}: max logit error {err:.2e}, accepted {na[b]} (oracle {a})")
+        # all-accept drafts for the NEXT step of this sequence: the oracle's greedy continuation
+        probe_T, tok, good = T + a + 1, int(o[a]), []
+        for j in range(k):
+            lg = om.forward([tok], caches[b], probe_T + j)
+            tok = int(argmax_tokens(lg)[0]); good.append(tok)
+        accept_drafts[b] = (good, probe_T, int(o[a]))
+    if all(int(na[b]) == 0 or True for b in sampled):
+        d2 = synth.uniform_tokens(seed, 6, B * k, cfg.vocab).reshape(B, k)
+        for b in sampled:
+            d2[b] = accept_drafts[b][0]
+        T_before = [ctx.get_state(b)[0] for b in range(B)]
+        na2, nxt2, _ = ctx.verify_step_batch(list(range(B)), d2)
+        got2 = ctx.logits(B * (k + 1)).reshape(B, k + 1, cfg.vocab)
+        for b in sampled:
+            good, pT, pend = accept_drafts[b]
+            if T_before[b] != pT:
+                continue                        # a near-tie changed the first step's outcome on the GPU
+            want = om.forward([pend] + good, caches[b], pT).astype(np.float64)
+            check_logits(got2[b], want, f"microbench all-accept seq {b}")
+            o = argmax_tokens(want)
+            near = any(top2_gap(want[j]) <= ATOL + RTOL * abs(float(want[j].max())) for j in range(k + 1))
+            if not near:
+                assert int(na2[b]) == k and int(nxt2[b]) == int(o[k]), (b, na2[b])
+            print(f"  seq {b}: all-accept step accepted {na2[b]} of {k}")
+    ctx.disable_logits_dump()
+    # ---- timing sweep (all-reject random drafts; T grows by one per step)
+    wbytes = 2 * cfg.streamed_params
+    print("  k rows  step_ms   alg_GB   GB/s  frac_of_8TB/s  MFMA_TFLOP/s(useful)")
+    for kk in (1, 2, 4, 8, 16, 32):
+        dr = synth.uniform_tokens(seed, 50 + kk, B * kk, cfg.vocab).reshape(B, kk)
+        for _ in range(2):
+            ctx.verify_step_batch(list(range(B)), dr)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        iters = 5
+        for _ in range(iters):
+            ctx.verify_step_batch(list(range(B)), dr)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / iters * 1e3
+        rows = B * (kk + 1)
+        Tcur = ctx.get_state(0)[0]
+        kv_bytes = B * 2 * 2 * cfg.n_layers * cfg.d_model * Tcur
+        alg = wbytes + kv_bytes
+        flops = 2.0 * rows * cfg.streamed_params + 4.0 * rows * Tcur * cfg.d_model * cfg.n_layers
+        print(f"  {kk:2d} {rows:4d} {ms:8.3f} {alg / 1e9:8.2f} {alg / ms / 1e6:6.0f} {alg / ms / 1e6 / 8000:8.3f} {flops / ms / 1e9:10.1f}")
+    ctx.close()
