@@ -47,9 +47,13 @@ __device__ __forceinline__ f32x4 mfma16x16x32(u32x4 a, u32x4 b, f32x4 c) {
 // ---- tiled activation layout (bf16) ---------------------------------------------------------
 // Activations X[rows][K] that feed a GEMM are stored as the matching B-operand images, one
 // plane for the hi part and one for the lo part of each value: block (t, ks) of 1 KiB holds rows
-// 16 t .. 16 t+15, columns 32 ks .. +31; lane l owns X[16 t + l%16][32 ks + 8 (l/16) .. +7].
+// 16 t .. 16 t+15, columns 32 ks .. +31; lane l owns X[16 t + l%16][32 ks + 8 (l/16) .. +7] and
+// finds it in the block's 16-byte piece xtile_piece(l) = 4 (l%16) + l/16: the pieces of a row are
+// adjacent (64 bytes), so a step with r live rows in a tile touches only the first 64 r bytes of
+// each block (lanes of rows past the end do not load at all).
+__host__ __device__ __forceinline__ int xtile_piece(int lane) { return ((lane & 15) << 2) | (lane >> 4); }
 __host__ __device__ __forceinline__ size_t xtile_off(int row, int col, int KSp) {
-    return ((size_t)((row >> 4) * KSp + (col >> 5)) * 64 + (size_t)(((col & 31) >> 3) * 16 + (row & 15))) * 8 + (col & 7);
+    return ((size_t)((row >> 4) * KSp + (col >> 5)) * 64 + (size_t)((row & 15) * 4 + ((col & 31) >> 3))) * 8 + (col & 7);
 }
 
 // ---- KV cache layout (bf16), per (slot, head): max_seq x head_dim elements per plane ---------

@@ -295,10 +295,18 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, const GemmPlan 
 // next batch in flight while the current one feeds the MFMAs; B operands come straight from the
 // tiled activation planes (1 KiB contiguous per k-step and plane, shared through L2 by all
 // workgroups); the waves' partial sums meet in LDS and are added in wave order; the first FT
-// waves run the fused epilogue.  FT and the wave count depend on the matrix shape only.
+// waves run the fused epilogue.  FT and the number of K slices depend on the matrix shape only, so
+// the order of every sum is the same for any number of rows; with several feature tiles AND several
+// row tiles a wave takes two K slices one after the other (half the waves, twice the registers).
 // ---------------------------------------------------------------------------------------------
+template <int NT, int FT>
+struct TileKShape {
+    static constexpr int SL = (FT > 1 && NT > 1) ? 2 : 1;            // K slices per wave
+    static constexpr int MAX_THREADS = (FT > 1 && NT == 1) ? 1024 : 512;
+};
 template <int NT, int EPI, bool SPLIT, int FT>
-__global__ __launch_bounds__(1024) void gemm_tilek_bf16(GemmArgs a) {
+__global__ __launch_bounds__((TileKShape<NT, FT>::MAX_THREADS)) void gemm_tilek_bf16(GemmArgs a) {
+    constexpr int SL = TileKShape<NT, FT>::SL;
     constexpr int TILES = (EPI == EPI_SWIGLU) ? 2 : 1;
     constexpr int AT = FT * TILES;                 // weight tiles per k-step
 #ifndef TK_UB_SMALL
@@ -307,13 +315,13 @@ __global__ __launch_bounds__(1024) void gemm_tilek_bf16(GemmArgs a) {
 #endif
     constexpr int UB = (AT * NT >= 4) ? TK_UB_BIG : TK_UB_SMALL;     // k-steps per load batch
     constexpr int PL = SPLIT ? 2 : 1;
-    extern __shared__ f32x4 red[];                 // [W][AT][NT][64], then rstd[16*NT] floats
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, W = blockDim.x >> 6;
+    extern __shared__ f32x4 red[];                 // [S][AT][NT][64], then rstd[16*NT] floats
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, S = (blockDim.x >> 6) * SL;
     const GemmPlan &p = a.plan;
     const int KSp = p.KSp;
     const int task0 = blockIdx.x * FT;
-    const int ks0 = (int)(((long)KSp * wave) / W), ks1 = (int)(((long)KSp * (wave + 1)) / W);
-    float *rstd_s = (float *)(red + (size_t)W * AT * NT * 64);
+    int ks1 = 0;                                   // end of the K slice being streamed
+    float *rstd_s = (float *)(red + (size_t)S * AT * NT * 64);
 
     const u32x4 *wp[AT];
 #pragma unroll
@@ -324,7 +332,10 @@ __global__ __launch_bounds__(1024) void gemm_tilek_bf16(GemmArgs a) {
             task = task < p.tasks ? task : p.tasks - 1;          // ragged last workgroup: recompute the last tile
             wp[f * TILES + i] = (const u32x4 *)a.W + ((size_t)(task + i * p.tasks) * KSp) * 64 + lane;
         }
-    const u32x4 *xh = (const u32x4 *)a.Xhi + lane, *xl = (const u32x4 *)a.Xlo + lane;
+    const u32x4 *xh = (const u32x4 *)a.Xhi, *xl = (const u32x4 *)a.Xlo;
+    int xpc[NT];                                   // lanes of rows past the end re-read the tile's first row:
+#pragma unroll                                     // no extra cache line, no divergence; their results are dropped
+    for (int t = 0; t < NT; ++t) xpc[t] = (t * 16 + (lane & 15) < a.rows) ? xtile_piece(lane) : (lane >> 4);
 
     auto issue = [&](int ks, u32x4 (&av)[AT][UB], u32x4 (&bv)[PL][NT][UB]) {
 #pragma unroll
@@ -335,16 +346,12 @@ __global__ __launch_bounds__(1024) void gemm_tilek_bf16(GemmArgs a) {
             for (int i = 0; i < AT; ++i) av[i][u] = __builtin_nontemporal_load(wp[i] + (size_t)k * 64);
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
-                bv[0][t][u] = xh[((size_t)t * KSp + k) * 64];
-                if (SPLIT) bv[PL - 1][t][u] = xl[((size_t)t * KSp + k) * 64];
+                bv[0][t][u] = xh[((size_t)t * KSp + k) * 64 + xpc[t]];
+                if (SPLIT) bv[PL - 1][t][u] = xl[((size_t)t * KSp + k) * 64 + xpc[t]];
             }
         }
     };
     f32x4 acc[AT][NT];
-#pragma unroll
-    for (int i = 0; i < AT; ++i)
-#pragma unroll
-        for (int t = 0; t < NT; ++t) acc[i][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
     auto compute = [&](int ks, u32x4 (&av)[AT][UB], u32x4 (&bv)[PL][NT][UB]) {
 #pragma unroll
         for (int u = 0; u < UB; ++u)
@@ -360,7 +367,9 @@ __global__ __launch_bounds__(1024) void gemm_tilek_bf16(GemmArgs a) {
     };
 
     u32x4 avA[AT][UB], bvA[PL][NT][UB], avB[AT][UB], bvB[PL][NT][UB];
-    int ks = ks0;
+    int slice = wave * SL;
+    int ks = (int)(((long)KSp * slice) / S);
+    ks1 = (int)(((long)KSp * (slice + 1)) / S);
     if (ks < ks1) issue(ks, avA, bvA);
     // epilogue inputs and rstd while the first batch is in flight
     EpiIn<NT> in;
@@ -392,20 +401,33 @@ __global__ __launch_bounds__(1024) void gemm_tilek_bf16(GemmArgs a) {
             if (i == 0) rstd_s[r] = 1.0f / sqrtf(ss / (float)(a.ssq_tiles * 16) + a.eps);
         }
     }
-    while (ks < ks1) {
-        if (ks + UB < ks1) issue(ks + UB, avB, bvB);
-        compute(ks, avA, bvA);
-        ks += UB;
-        if (ks >= ks1) break;
-        if (ks + UB < ks1) issue(ks + UB, avA, bvA);
-        compute(ks, avB, bvB);
-        ks += UB;
+#pragma unroll
+    for (int sl = 0; sl < SL; ++sl) {
+        if (sl > 0) {
+            slice = wave * SL + sl;
+            ks = (int)(((long)KSp * slice) / S);
+            ks1 = (int)(((long)KSp * (slice + 1)) / S);
+            if (ks < ks1) issue(ks, avA, bvA);
+        }
+#pragma unroll
+        for (int i = 0; i < AT; ++i)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) acc[i][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        while (ks < ks1) {
+            if (ks + UB < ks1) issue(ks + UB, avB, bvB);
+            compute(ks, avA, bvA);
+            ks += UB;
+            if (ks >= ks1) break;
+            if (ks + UB < ks1) issue(ks + UB, avA, bvA);
+            compute(ks, avB, bvB);
+            ks += UB;
+        }
+        // ---- the slices' partial sums meet in LDS and are added in slice order
+#pragma unroll
+        for (int i = 0; i < AT; ++i)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) red[((slice * AT + i) * NT + t) * 64 + lane] = acc[i][t];
     }
-    // ---- the waves' partial sums meet in LDS and are added in wave order
-#pragma unroll
-    for (int i = 0; i < AT; ++i)
-#pragma unroll
-        for (int t = 0; t < NT; ++t) red[((wave * AT + i) * NT + t) * 64 + lane] = acc[i][t];
     __syncthreads();
     if (!finisher) return;
     f32x4 sum[TILES][NT];
@@ -414,7 +436,7 @@ __global__ __launch_bounds__(1024) void gemm_tilek_bf16(GemmArgs a) {
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             f32x4 v = red[((0 * AT + wave * TILES + i) * NT + t) * 64 + lane];
-            for (int w = 1; w < W; ++w) v += red[((w * AT + wave * TILES + i) * NT + t) * 64 + lane];
+            for (int w = 1; w < S; ++w) v += red[((w * AT + wave * TILES + i) * NT + t) * 64 + lane];
             sum[i][t] = v;
         }
     gemm_epilogue<NT, EPI, TILES>(a, p, my_task, lane, sum, rstd_s, in);
@@ -424,8 +446,9 @@ template <int NT, int EPI, int FT>
 static void launch_tilek(const GemmArgs &a, hipStream_t st) {
     constexpr int TILES = (EPI == EPI_SWIGLU) ? 2 : 1;
     const GemmPlan &p = a.plan;
-    const int W = p.tk_waves;
-    const size_t lds = (size_t)W * FT * TILES * NT * 1024 + 256;
+    const int S = (FT == 1 && p.tk_waves > 8) ? 8 : p.tk_waves;      // K slices (single-tile kernels are built for 8 waves)
+    const int W = S / TileKShape<NT, FT>::SL;
+    const size_t lds = (size_t)S * FT * TILES * NT * 1024 + 256;
     dim3 grid((p.tasks + FT - 1) / FT), block(W * 64);
     if (a.split) {
         static bool attr_done = false;
@@ -468,7 +491,7 @@ static void launch_gemm_nt(const GemmArgs &a, hipStream_t st) {
 // Panel GEMM for prompt processing (hundreds of rows): a workgroup computes a block of
 // 4*FT feature tiles x RT row tiles over the whole K axis -- no K split, no partial sums.  The
 // block's activation rows are staged through LDS in chunks of KC k-steps (double-buffered,
-// straight copies because the planes are already in B-operand order) and shared by the four
+// 16-byte pieces gathered from the planes' row-major piece order into lane order) and shared by the
 // waves; every wave streams the weight blocks of its own FT feature tiles (TILES each) from
 // global memory / L2, where the workgroups of the other row blocks find them again.  MFMA-bound
 // by design: FT*TILES*RT*2 MFMAs per k-step and wave against RT*2 LDS operand reads.
@@ -534,7 +557,7 @@ __global__ __launch_bounds__(WV * 64) void gemm_panel_bf16(GemmArgs a0) {
                 int k = kc * KC + kk;
                 k = k < KSp ? k : KSp - 1;
                 const int tt = (rt0 + t < n_rt_total) ? rt0 + t : 0;
-                const size_t src = ((size_t)tt * KSp + k) * 64 + ln;
+                const size_t src = ((size_t)tt * KSp + k) * 64 + xtile_piece(ln);   // LDS holds the block in lane order
                 v[j] = pl ? xl[src] : xh[src];
             }
         }
