@@ -730,6 +730,12 @@ GemmPlan make_gemm_plan(int N, int K, int tiles_per_task) {
     return p;
 }
 
+// Keeps the loads written above this point above it: the compiler may not sink a load into the
+// branch that uses its value past something that could write memory.  No value is consumed here,
+// so nothing waits.  Used where many loads must be in flight before a dependent value (the
+// sequence length) arrives.
+__device__ __forceinline__ void loads_stay_above() { asm volatile("" ::: "memory"); }
+
 // =============================================================================================
 // causal attention of m <= 16*NTQ query rows of one sequence over its KV cache
 // =============================================================================================
@@ -771,15 +777,28 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
             for (int s = 0; s < KSTEPS; ++s) {
                 const size_t off = (size_t)(key0 / 16 + t) * (16 * DH) + s * 512 + lane * 8;
                 ka[t][s] = *(const u32x4 *)(kh + off);
-                if (KVS) kb[t][s] = *(const u32x4 *)(kl + off);
+                if (KVS) kb[t][s] = (*(const u32x4 *)(kl + off));
             }
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
             const size_t off = (size_t)(key0 / 32) * (32 * DH) + dt * 512 + lane * 8;
-            va[dt] = *(const u32x4 *)(vh + off);
-            if (KVS) vb[dt] = *(const u32x4 *)(vl + off);
+            va[dt] = (*(const u32x4 *)(vh + off));
+            if (KVS) vb[dt] = (*(const u32x4 *)(vl + off));
         }
     }
+    // a single row tile's query operands do not depend on the sequence length either
+    u32x4 qh0[KSTEPS], ql0[KSTEPS];
+    if (NTQ == 1) {
+        const int j = j0 + n;
+        const int r = b * m + (j < m ? j : 0);
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s) {
+            const size_t off = xtile_off(r, h * DH + s * 32 + g * 8, d_model / 32);
+            qh0[s] = (*(const u32x4 *)((const bf16_t *)a.Qhi + off));
+            ql0[s] = (*(const u32x4 *)((const bf16_t *)a.Qlo + off));
+        }
+    }
+    loads_stay_above();
     const int T = a.T[slot];
     const int kv_len = T + j0 + m_blk;                  // positions the block's last row can see
     if (chunk0 >= kv_len) return;                       // uniform for the workgroup
@@ -805,6 +824,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
             u32x4 qh[KSTEPS], ql[KSTEPS];
 #pragma unroll
             for (int s = 0; s < KSTEPS; ++s) {
+                if (NTQ == 1) { qh[s] = qh0[s]; ql[s] = ql0[s]; continue; }
                 const size_t off = xtile_off(r, h * DH + s * 32 + g * 8, d_model / 32);
                 qh[s] = *(const u32x4 *)((const bf16_t *)a.Qhi + off);
                 ql[s] = *(const u32x4 *)((const bf16_t *)a.Qlo + off);
@@ -897,40 +917,49 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
 
 // merges the chunk partials of one (row, head): out = sum_c e^{m_c - M} O_c / sum_c e^{m_c - M} l_c,
 // over the chunks that contain positions <= the row's own, in chunk order; writes hi/lo tiled planes.
-// One thread per 4 output features; loads are issued 8 chunks at a time.
+// One thread per 4 output features; the partials of 16 chunks are in flight at a time.
 template <int DH>
 __global__ void attn_combine_bf16_kernel(AttnArgs a, int rq) {
+    constexpr int CB = 16;                             // chunks per load batch
     const int r = blockIdx.x, h = blockIdx.y;
     const int b = r / a.m, j = r % a.m;
-    const int slot = a.batch_slots[b];
-    const int pos = a.T[slot] + j;
-    const int nc = pos / ATTN_CHUNK + 1;
+    const int slot = a.slot_const >= 0 ? a.slot_const : a.batch_slots[b];
     const int d4 = threadIdx.x;                        // features 4 d4 .. +3
     const size_t base = ((size_t)b * a.H + h) * a.n_chunks;
-    float M = LLMA_NEG_INF;
-    for (int c0 = 0; c0 < nc; c0 += 8) {
-        float mv[8];
+    // the first batch of partials is requested before the row's position is known: every launched
+    // chunk has storage, and what a chunk past the row's last one holds is dropped below
+    float mv[CB], lv[CB];
+    f32x4 ov[CB];
+    auto fetch = [&](int c0) {
 #pragma unroll
-        for (int u = 0; u < 8; ++u) mv[u] = (c0 + u < nc) ? a.pm[(base + c0 + u) * rq + j] : LLMA_NEG_INF;
-#pragma unroll
-        for (int u = 0; u < 8; ++u) M = fmaxf(M, mv[u]);
-    }
-    float L = 0.f;
+        for (int u = 0; u < CB; ++u) {
+            const int c = (c0 + u < a.n_chunks) ? c0 + u : a.n_chunks - 1;
+            mv[u] = a.pm[(base + c) * rq + j];
+            lv[u] = a.pl[(base + c) * rq + j];
+            ov[u] = (*(const f32x4 *)(a.po + ((base + c) * rq + j) * DH + d4 * 4));
+        }
+    };
+    fetch(0);
+    loads_stay_above();
+    const int pos = a.T[slot] + j;
+    const int nc = pos / ATTN_CHUNK + 1;
+    // running (max, sum, O) over the chunks in chunk order
+    float M = LLMA_NEG_INF, L = 0.f;
     f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
-    for (int c0 = 0; c0 < nc; c0 += 8) {
-        float mv[8], lv[8];
-        f32x4 ov[8];
+    for (int c0 = 0; c0 < nc; c0 += CB) {
+        if (c0 > 0) fetch(c0);
+        float Mb = M;
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
-            if (c0 + u < nc) {
-                mv[u] = a.pm[(base + c0 + u) * rq + j];
-                lv[u] = a.pl[(base + c0 + u) * rq + j];
-                ov[u] = *(const f32x4 *)(a.po + ((base + c0 + u) * rq + j) * DH + d4 * 4);
-            }
+        for (int u = 0; u < CB; ++u)
+            if (c0 + u < nc) Mb = fmaxf(Mb, mv[u]);
+        const float rs = (M == LLMA_NEG_INF) ? 0.f : __expf(M - Mb);
+        L *= rs;
+        acc *= rs;
+        M = Mb;
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
+        for (int u = 0; u < CB; ++u)
             if (c0 + u < nc) {
-                const float w = __expf(mv[u] - M);
+                const float w = (mv[u] == LLMA_NEG_INF) ? 0.f : __expf(mv[u] - M);
                 L += w * lv[u];
                 acc += ov[u] * w;
             }
