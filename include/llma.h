@@ -170,6 +170,12 @@ int llma_set_option(llma_ctx *ctx, int32_t option, int32_t value);
 /* Sums the event pairs recorded since the last call: *launches = number of gate/up GEMM
  * launches, *total_ms = their summed duration.  Synchronises the stream. */
 int llma_get_kernel_timing(llma_ctx *ctx, int64_t *launches, double *total_ms);
+/* Mean duration in microseconds of the FFN gate/up GEMM of a decoding step with `rows` rows
+ * (1..48): `reps` launches back to back on the context's stream, cycling through the layers'
+ * own matrices (so every launch streams its weights from HBM), one event pair around all of
+ * them.  The activations are whatever the context's scratch holds; outputs go to scratch.
+ * bf16 models only.  Synchronises the stream.  For the roofline figure of the benchmark. */
+int llma_time_ffn_gemm(llma_ctx *ctx, int32_t rows, int32_t reps, double *mean_us);
 /* Device bytes the context holds (weights, KV cache, scratch). */
 int64_t llma_device_bytes(const llma_ctx *ctx);
 

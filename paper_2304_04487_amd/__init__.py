@@ -24,7 +24,7 @@ EXPORTS = [
     "llma_create", "llma_destroy", "llma_last_error", "llma_reset", "llma_prefill", "llma_get_state",
     "llma_set_pending", "llma_kv_import", "llma_find_trigger", "llma_verify_step",
     "llma_verify_step_batch", "llma_generate", "llma_set_logits_dump", "llma_set_option",
-    "llma_get_kernel_timing", "llma_device_bytes",
+    "llma_get_kernel_timing", "llma_time_ffn_gemm", "llma_device_bytes",
 ]
 
 
@@ -80,6 +80,7 @@ def load_library() -> ctypes.CDLL:
     lib.llma_set_logits_dump.argtypes = [vp, vp, c_int32]
     lib.llma_set_option.argtypes = [vp, c_int32, c_int32]
     lib.llma_get_kernel_timing.argtypes = [vp, POINTER(c_int64), POINTER(c_double)]
+    lib.llma_time_ffn_gemm.argtypes = [vp, c_int32, c_int32, POINTER(c_double)]
     lib.llma_device_bytes.argtypes = [vp]
     lib.llma_device_bytes.restype = c_int64
     _lib = lib
@@ -237,6 +238,11 @@ class Context:
         n, ms = c_int64(), c_double()
         self._ck(self.lib.llma_get_kernel_timing(self._h, byref(n), byref(ms)))
         return n.value, ms.value
+
+    def time_ffn_gemm(self, rows: int, reps: int) -> float:
+        us = c_double()
+        self._ck(self.lib.llma_time_ffn_gemm(self._h, rows, reps, byref(us)))
+        return us.value
 
     def device_bytes(self) -> int:
         return int(self.lib.llma_device_bytes(self._h))

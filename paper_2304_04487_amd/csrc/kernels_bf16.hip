@@ -798,7 +798,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
             ql0[s] = (*(const u32x4 *)((const bf16_t *)a.Qlo + off));
         }
     }
-    loads_stay_above();
+    if (NTQ == 1) loads_stay_above();                   // (with more row tiles the registers are needed elsewhere)
     const int T = a.T[slot];
     const int kv_len = T + j0 + m_blk;                  // positions the block's last row can see
     if (chunk0 >= kv_len) return;                       // uniform for the workgroup

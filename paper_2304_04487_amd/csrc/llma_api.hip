@@ -472,10 +472,13 @@ static void drop_graphs(llma_ctx *c) {
 }
 
 static int run_step(llma_ctx *c, int kind, int n_seqs, int m, int t_max, int slot) {
-    // attention chunks launched: enough for the longest sequence, in buckets of 4 so that the
-    // launch shape (and with it the graph) changes only every 4 * ATTN_CHUNK positions
+    // attention chunks launched: enough for the longest sequence.  A launched chunk streams its K/V
+    // blocks before it knows whether it lies past the sequence's end, so the count is rounded up
+    // (fewer distinct launch shapes, i.e. graphs) only by a few percent: to whole buckets of 1, 4 or
+    // 16 chunks for up to 32, 128 or more chunks
     int n_chunks = (t_max + m + ATTN_CHUNK - 1) / ATTN_CHUNK;
-    n_chunks = (n_chunks + 3) / 4 * 4;
+    const int bucket = n_chunks <= 32 ? 1 : (n_chunks <= 128 ? 4 : 16);
+    n_chunks = (n_chunks + bucket - 1) / bucket * bucket;
     if (c->bf16 && n_chunks > c->nc_max) n_chunks = c->nc_max;
     c->run_st = c->st;
     if (!c->opt_graph || c->opt_timing || c->graphs.size() > 256) return step_body(c, kind, n_seqs, m, n_chunks, slot);
@@ -827,6 +830,40 @@ extern "C" int llma_set_option(llma_ctx *c, int32_t option, int32_t value) {
         case LLMA_OPT_USE_GRAPH: c->opt_graph = value ? 1 : 0; return LLMA_OK;
         default: return fail(c, LLMA_E_INVAL, "llma_set_option: unknown option %d", option);
     }
+}
+
+extern "C" int llma_time_ffn_gemm(llma_ctx *c, int32_t rows, int32_t reps, double *mean_us) {
+    if (!c || !mean_us) return fail(c, LLMA_E_INVAL, "llma_time_ffn_gemm: null argument");
+    if (c->cfg.dtype != LLMA_DTYPE_BF16) return fail(c, LLMA_E_INVAL, "llma_time_ffn_gemm: bf16 models only");
+    if (rows < 1 || rows > 48 || rows > c->cfg.max_batch * (c->cfg.max_k + 1) || reps < 1 || reps > 100000)
+        return fail(c, LLMA_E_RANGE, "llma_time_ffn_gemm: rows %d (1..min(48, max_batch (max_k + 1))) or reps %d (1..100000) out of range", rows, reps);
+    const llma_model_cfg &g = c->cfg;
+    GemmArgs ga{};
+    ga.rows = rows; ga.split = c->opt_split; ga.eps = g.rms_eps; ga.rstd_in = c->rstd;
+    ga.ssq_tiles = g.d_model / 16; ga.H = g.n_heads; ga.dh = g.head_dim; ga.max_seq = c->seq_cap; ga.nx_KSp = c->plan_qkv.KSp;
+    ga.plan = c->plan_gu; ga.Xhi = c->xhi; ga.Xlo = c->xlo; ga.epi = EPI_SWIGLU; ga.ssq_in = c->ssq;
+    ga.act_hi = c->act_hi; ga.act_lo = c->act_lo; ga.act_KSp = c->plan_down.KSp;
+    hipEvent_t e0, e1;
+    HIP_TRY(c, hipEventCreate(&e0));
+    HIP_TRY(c, hipEventCreate(&e1));
+    HIP_TRY(c, hipStreamSynchronize(c->st));
+    for (int pass = 0; pass < 2; ++pass) {              // pass 0 warms up (first-launch set-up of the kernel)
+        const int n = pass ? reps : (reps < g.n_layers ? reps : g.n_layers);
+        HIP_TRY(c, hipEventRecord(e0, c->st));
+        for (int r = 0; r < n; ++r) {
+            ga.W = c->wgu[r % g.n_layers];
+            launch_gemm_bf16(ga, c->st);
+        }
+        HIP_TRY(c, hipEventRecord(e1, c->st));
+        HIP_TRY(c, hipEventSynchronize(e1));
+    }
+    HIP_TRY(c, hipGetLastError());
+    float ms = 0.f;
+    HIP_TRY(c, hipEventElapsedTime(&ms, e0, e1));
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    *mean_us = (double)ms * 1e3 / reps;
+    return LLMA_OK;
 }
 
 extern "C" int llma_get_kernel_timing(llma_ctx *c, int64_t *launches, double *total_ms) {
