@@ -106,7 +106,7 @@ int llma_set_pending(llma_ctx *ctx, int32_t seq, int32_t token);
 int llma_kv_import(llma_ctx *ctx, int32_t seq, int32_t layer, const void *k, const void *v, int32_t len);
 
 /* --- the three calls of the method ---------------------------------------------------- */
-/* Trigger (paper: Method, the n-gram match of Algorithm 1 line 3).  Stateless; all
+/* Trigger (paper: Method, the n-gram match step of Algorithm 1).  Stateless; all
  * pointers HOST; the scan itself runs on the current HIP device.
  *   y[0..y_len): output tokens generated so far.  ref: the documents' tokens, flat;
  *   doc_offsets int32[n_docs+1], non-decreasing, doc j = ref[doc_offsets[j] .. doc_offsets[j+1]).
@@ -120,7 +120,7 @@ int llma_find_trigger(const int32_t *y, int32_t y_len,
                       const int32_t *ref, const int32_t *doc_offsets, int32_t n_docs,
                       int32_t n, int32_t *doc_out, int32_t *pos_out);
 
-/* One verification step (paper: Eq. 3 and Algorithm 1 lines 10-17) for slot `seq`.
+/* One verification step (paper: Eq. 3 and the draft-comparison loop of Algorithm 1) for slot `seq`.
  * draft: HOST int32[k], the copied tokens d_pos..d_pos+k-1; 0 <= k <= max_k; k = 0 is a
  * plain greedy step (Eq. 2).  The rows [pending, draft[0..k)] go through the model at
  * positions T..T+k in one causal forward, giving o_0..o_k (vocabulary arg max per row,

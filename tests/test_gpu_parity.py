@@ -1,6 +1,6 @@
 """GPU parity: the HIP path through the C ABI against the CPU oracle on the same seeded inputs.
 
-Bars (written here, derived in the design doc):
+Bars:
   - trigger positions, accepted counts, step traces, token ids: bit-exact;
   - logits: |gpu - oracle| <= 1e-2 + 2e-2*|oracle| for bf16 models, <= 1e-4 + 1e-4*|oracle| for
     fp32 models (oracle in float64);
