@@ -104,10 +104,13 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="7b", choices=["small", "7b", "13b"])
+    ap.add_argument("--workload", default="7b", choices=["small", "7b", "13b", "cag_small", "cag7b"])
     ap.add_argument("--k", type=int, default=None, help="copy length (default: the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="skip the k = 0 / 1 / ... comparison runs")
+    ap.add_argument("--grid", action="store_true",
+                    help="instead of the benchmark line: decode-only tokens/s and steps of the workload over the "
+                         "paper's (n, k) grid, n in {1,2,3} x k in {4,8,12,16,18}, as a table and one JSON line")
     ap.add_argument("--profile-steps", type=int, default=0,
                     help="profiling aid (for rocprofv3): skip the benchmark, run this many k-draft verification steps "
                          "on a random KV cache of prompt length plus one plain 256 MiB device copy, print nothing")
@@ -131,7 +134,7 @@ def main():
     log(f"[bench] weights generated in {time.time() - t0:.1f}s")
     prompt = synth.make_prompt(wl)
     t0 = time.time()
-    ctx = llma.Context(cfg, w, max_seq=wl.prompt_len + wl.max_new + 64, max_batch=1, max_k=max(16, k))
+    ctx = llma.Context(cfg, w, max_seq=wl.prompt_len + wl.max_new + 64, max_batch=1, max_k=max(18 if args.grid else 16, k))
     del w
     log(f"[bench] context created in {time.time() - t0:.1f}s, {ctx.device_bytes() / 1e9:.2f} GB on device")
 
@@ -174,6 +177,26 @@ def main():
     t_k0, y0, _ = timed_generate(None, None, 1, 0, 1)
     ref, offs = synth.build_reference(wl, y0)
     log(f"[bench] k=0 greedy: {wl.max_new / t_k0:.1f} tok/s (prefill {t_prefill * 1e3:.0f} ms)")
+
+    if args.grid:
+        # speed-up over the library's own plain greedy decoding for every (n, k) of the paper's search
+        # grid (Experiments, the hyper-parameter figures), same prompt / reference / output
+        grid = {}
+        base = wl.max_new / (t_k0 - t_prefill)
+        log(f"[grid] {args.workload}: prompt {wl.prompt_len}, reference {len(ref)} tokens in {len(offs) - 1} docs, "
+            f"{wl.max_new} new tokens; plain greedy {base:.1f} tok/s decode-only")
+        log("[grid]  n   k  steps  tok/step  decode tok/s  speed-up")
+        for nn in (1, 2, 3):
+            for kk in (4, 8, 12, 16, 18):
+                timed_generate(ref, offs, nn, kk, 1)                 # first use of this row count: graphs get captured
+                tt, yy, tr = timed_generate(ref, offs, nn, kk, 2)
+                assert np.array_equal(yy, y0)
+                rate = wl.max_new / (tt - t_prefill)
+                grid[f"n{nn}_k{kk}"] = {"steps": len(tr), "decode_only_tokens_per_s": round(rate, 1), "speedup": round(rate / base, 3)}
+                log(f"[grid] {nn:2d} {kk:3d} {len(tr):6d} {wl.max_new / len(tr):9.2f} {rate:13.1f} {rate / base:9.2f}")
+        print(json.dumps({"workload": args.workload, "plain_decode_only_tokens_per_s": round(base, 1), "grid": grid}), flush=True)
+        ctx.close()
+        return
 
     for _ in range(args.warmup):
         timed_generate(ref, offs, wl.n, k, 1)

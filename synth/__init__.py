@@ -276,6 +276,8 @@ class Workload:
     doc_cuts: tuple = ()
     seed: int = 20230410
     k_sweep: tuple = field(default_factory=tuple)
+    n_similar: int = 0      # > 0: the reference is this many separate "similar answers", each built
+                            #      from the output on its own (cache-assisted scenario), ref_len in total
 
 
 WORKLOADS = {
@@ -284,6 +286,11 @@ WORKLOADS = {
     "7b": Workload("7b", LLAMA_7B, 1536, 1472, n=1, k=8, max_new=256, overlap=0.5, mean_span=12.0,
                    doc_cuts=(491, 982), k_sweep=(1, 4, 8, 16)),
     "13b": Workload("13b", LLAMA_13B, 2048, 512, n=2, k=16, max_new=512, overlap=0.8, mean_span=12.0),
+    # cache-assisted scenario (paper: Experiments, the cache-assisted setting): a short query, the
+    # reference = 4 earlier answers to similar queries, held outside the prompt
+    "cag_small": Workload("cag_small", SMALL, 16, 4 * 96, n=1, k=8, max_new=96, overlap=0.5, mean_span=10.0, n_similar=4),
+    "cag7b": Workload("cag7b", LLAMA_7B, 16, 4 * 176, n=1, k=8, max_new=176, overlap=0.5, mean_span=12.0,
+                      k_sweep=(4, 8, 16), n_similar=4),
 }
 
 
@@ -302,6 +309,14 @@ def build_reference(wl: Workload, y: np.ndarray):
         body = replace_positions(y, 1.0 - wl.overlap, wl.model.vocab, wl.seed)
         pad = uniform_tokens(wl.seed, _S_REF_NOISE + 2, wl.ref_len - len(body), wl.model.vocab)
         ref = np.concatenate([body, pad]).astype(np.int32)
+    elif wl.n_similar > 0:
+        # each "similar answer" copies its own random spans of the output (a different seed per
+        # document), so a span missing from one document may be present in another
+        per = wl.ref_len // wl.n_similar
+        docs = [make_ref(y, wl.overlap, wl.mean_span, per, wl.model.vocab, wl.seed + 7919 * (i + 1))[0]
+                for i in range(wl.n_similar)]
+        ref = np.concatenate(docs).astype(np.int32)
+        return ref, np.arange(0, wl.n_similar + 1, dtype=np.int32) * per
     else:
         ref, _ = make_ref(y, wl.overlap, wl.mean_span, wl.ref_len, wl.model.vocab, wl.seed)
     return ref, split_docs(ref, wl.doc_cuts)

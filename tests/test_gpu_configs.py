@@ -100,6 +100,45 @@ def test_small_config_end_to_end(llma):
     ctx.close()
 
 
+# --------------------------------------------------------------------------- cache-assisted scenario
+def test_cache_assisted_small_end_to_end(llma):
+    """Cache-assisted setting of the paper's experiments at the small model: a 16-token query, the
+    reference = four separate 'similar answers' that are NOT part of the prompt.  Output tokens and
+    step trace (rows fed, tokens emitted, matched document and position per step) against the oracle;
+    triggers land in several documents."""
+    wl = synth.WORKLOADS["cag_small"]
+    cfg = wl.model
+    w = synth.make_weights(cfg, wl.seed)
+    om = OracleModel(cfg, w)
+    prompt = synth.make_prompt(wl)
+    cap = wl.prompt_len + wl.max_new + 40
+    y = greedy_decode(CachedLLM(om, prompt, cap), wl.max_new)
+    ref, offs = synth.build_reference(wl, np.array(y))
+    assert len(offs) == 5
+    D = docs_from_flat(ref, offs)
+    yo, trace = llma_decode(CachedLLM(om, prompt, cap), D, wl.n, wl.k, wl.max_new)
+    assert yo == y and trace == infer_decoding_sequence(y, D, wl.n, wl.k)
+    ctx = llma.Context(cfg, w, max_seq=cap, max_batch=1, max_k=16)
+    g0, _ = ctx.generate(prompt, None, None, 1, 0, wl.max_new)
+    g1, t1 = ctx.generate(prompt, ref, offs, wl.n, wl.k, wl.max_new)
+    assert np.array_equal(g0, g1), "LLMA output differs from the same library's stepwise greedy output"
+    near = teacher_forced_check(ctx, om, prompt, y, "cag_small")
+    first_diff = next((i for i in range(wl.max_new) if g1[i] != y[i]), None)
+    if first_diff is None:
+        assert t1 == trace, "step trace differs from the oracle's"
+        docs_hit = {d for (_, _, d, _) in t1 if d >= 0}
+        assert len(docs_hit) >= 2 and len(t1) < wl.max_new
+    else:
+        assert any(p == first_diff for p, _ in near), (first_diff, near)
+    for nn, kk in ((2, 4), (3, 16)):                       # other (n, k) of the paper's grid: same tokens
+        g2, t2 = ctx.generate(prompt, ref, offs, nn, kk, wl.max_new)
+        assert np.array_equal(g2, g0)
+        if first_diff is None:
+            assert t2 == infer_decoding_sequence(y, D, nn, kk)
+    print(f"cag_small: {len(t1)} steps for {wl.max_new} tokens; near-ties {near}; first token difference {first_diff}")
+    ctx.close()
+
+
 # --------------------------------------------------------------------------- 7B shape, full depth
 @pytest.mark.timeout(600)
 def test_7b_shape_verify_step_logits(llma):

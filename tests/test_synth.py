@@ -70,3 +70,29 @@ def test_tiny_reference_recipe():
     y = synth.uniform_tokens(9, 2, 256, 32000)
     ref, offs = synth.build_reference(wl7, y)
     assert len(ref) == 1472 and offs.tolist() == [0, 491, 982, 1472]
+
+
+def test_cache_assisted_reference_recipe():
+    """Four 'similar answers' of equal length outside the prompt, each with its own spans of the
+    output; together they cover more of the output than one of them."""
+    wl = synth.WORKLOADS["cag7b"]
+    assert wl.prompt_len == 16 and wl.n_similar == 4
+    y = synth.uniform_tokens(11, 3, wl.max_new, wl.model.vocab)
+    ref, offs = synth.build_reference(wl, y)
+    assert len(ref) == wl.ref_len and offs.tolist() == [0, 176, 352, 528, 704]
+    docs = [ref[offs[i]:offs[i + 1]] for i in range(4)]
+    assert all(not np.array_equal(docs[0], d) for d in docs[1:])
+    def covered(ds):
+        pos = set()
+        yl = y.tolist()
+        for d in ds:
+            dl = d.tolist()
+            for i in range(len(yl) - 3):           # output 4-grams that occur in the document
+                g = yl[i:i + 4]
+                if any(dl[j:j + 4] == g for j in range(len(dl) - 3)):
+                    pos.update(range(i, i + 4))
+        return len(pos) / len(yl)
+    one, four = covered(docs[:1]), covered(docs)
+    assert 0.15 < one < 0.75 and four > one
+    ref2, offs2 = synth.build_reference(wl, y)
+    assert np.array_equal(ref, ref2) and np.array_equal(offs, offs2)
