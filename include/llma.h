@@ -154,6 +154,31 @@ int llma_generate(llma_ctx *ctx, int32_t seq, const int32_t *prompt, int32_t pro
                   int32_t *out_tokens, int32_t *n_out,
                   llma_step_rec *trace, int32_t *n_steps);
 
+/* The same decoding for n_seqs sequences at once (next step after the paper's batch-1
+ * set-up; every sequence follows Algorithm 1 on its own prompt and its own reference, the
+ * sequences share each pass over the weights).  Every step feeds k + 1 rows per sequence:
+ * a sequence's trigger decides how many of them are drafts (its trace records 1 + k_eff), a
+ * sequence that already has its max_new tokens idles.  All pointers HOST.
+ *   seqs            int32[n_seqs], distinct slots (each is reset)
+ *   prompts         the prompts back to back; prompt_offsets int32[n_seqs + 1], [0] = 0
+ *   refs            the references back to back (may be NULL if all are empty)
+ *   doc_offsets     the sequences' document-offset lists back to back, sequence b contributing
+ *                   n_docs[b] + 1 entries that start at 0 (relative to its own reference); may be
+ *                   NULL if n_docs is NULL or all zero
+ *   n_docs          int32[n_seqs] (NULL = no references: plain greedy)
+ *   out_tokens      int32[n_seqs * max_new], row b = sequence b; n_out int32[n_seqs]
+ *   trace           n_seqs * max_new records, row b = sequence b (may be NULL); n_steps
+ *                   int32[n_seqs] (may be NULL)
+ * Needs n_seqs <= max_batch and prompt length + max_new + k <= max_seq for every sequence.
+ * The tokens of a sequence are those the single-sequence call produces for it.
+ * Errors: INVAL, RANGE; on error before the first launch the context is unchanged. */
+int llma_generate_batch(llma_ctx *ctx, int32_t n_seqs, const int32_t *seqs,
+                        const int32_t *prompts, const int32_t *prompt_offsets,
+                        const int32_t *refs, const int32_t *doc_offsets, const int32_t *n_docs,
+                        int32_t n, int32_t k, int32_t max_new,
+                        int32_t *out_tokens, int32_t *n_out,
+                        llma_step_rec *trace, int32_t *n_steps);
+
 /* --- inspection / measurement --------------------------------------------------------- */
 /* When dev_buf != NULL every later forward also writes its rows' logits, fp32
  * [rows, vocab] row-major, to this DEVICE buffer (capacity_rows >= rows of the largest

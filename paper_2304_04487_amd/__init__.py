@@ -23,7 +23,7 @@ LLMA_OPT_ACT_SPLIT, LLMA_OPT_KERNEL_TIMING, LLMA_OPT_USE_GRAPH = 1, 2, 3
 EXPORTS = [
     "llma_create", "llma_destroy", "llma_last_error", "llma_reset", "llma_prefill", "llma_get_state",
     "llma_set_pending", "llma_kv_import", "llma_find_trigger", "llma_verify_step",
-    "llma_verify_step_batch", "llma_generate", "llma_set_logits_dump", "llma_set_option",
+    "llma_verify_step_batch", "llma_generate", "llma_generate_batch", "llma_set_logits_dump", "llma_set_option",
     "llma_get_kernel_timing", "llma_time_ffn_gemm", "llma_device_bytes",
 ]
 
@@ -77,6 +77,8 @@ def load_library() -> ctypes.CDLL:
     lib.llma_verify_step_batch.argtypes = [vp, c_int32, i32p, i32p, c_int32, i32p, i32p, i32p]
     lib.llma_generate.argtypes = [vp, c_int32, i32p, c_int32, i32p, i32p, c_int32, c_int32, c_int32, c_int32,
                                   i32p, i32p, POINTER(StepRec), i32p]
+    lib.llma_generate_batch.argtypes = [vp, c_int32, i32p, i32p, i32p, i32p, i32p, i32p, c_int32, c_int32, c_int32,
+                                        i32p, i32p, POINTER(StepRec), i32p]
     lib.llma_set_logits_dump.argtypes = [vp, vp, c_int32]
     lib.llma_set_option.argtypes = [vp, c_int32, c_int32]
     lib.llma_get_kernel_timing.argtypes = [vp, POINTER(c_int64), POINTER(c_double)]
@@ -216,6 +218,33 @@ class Context:
                                         _ptr(out), byref(n_out), tr, byref(n_steps)))
         trace = [(t.rows_in, t.emitted, t.doc, t.pos) for t in tr[:n_steps.value]]
         return out[:n_out.value], trace
+
+    def generate_batch(self, prompts, refs, n: int, k: int, max_new: int, seqs=None):
+        """One LLMA decoding per sequence, all sequences in the same steps.  prompts: list of id
+        arrays; refs: list of (ref, doc_offsets) or None per sequence.  Returns a list of
+        (tokens int32[max_new], trace) per sequence."""
+        B = len(prompts)
+        s = _i32(seqs if seqs is not None else list(range(B)))
+        ps = [_i32(p) for p in prompts]
+        poff = _i32(np.concatenate([[0], np.cumsum([len(p) for p in ps])]))
+        pcat = _i32(np.concatenate(ps))
+        rs, offs, nd = [], [], []
+        for r in refs:
+            if r is None:
+                rs.append(np.zeros(0, np.int32)); offs.append(np.zeros(1, np.int32)); nd.append(0)
+            else:
+                rs.append(_i32(r[0])); offs.append(_i32(r[1])); nd.append(len(offs[-1]) - 1)
+        rcat, ocat, ndv = _i32(np.concatenate(rs)), _i32(np.concatenate(offs)), _i32(nd)
+        out = np.zeros(B * max_new, np.int32)
+        n_out, n_steps = np.zeros(B, np.int32), np.zeros(B, np.int32)
+        tr = (StepRec * (B * max_new))()
+        self._ck(self.lib.llma_generate_batch(self._h, B, _ptr(s), _ptr(pcat), _ptr(poff), _ptr(rcat), _ptr(ocat), _ptr(ndv),
+                                              n, k, max_new, _ptr(out), _ptr(n_out), tr, _ptr(n_steps)))
+        res = []
+        for b in range(B):
+            trace = [(t.rows_in, t.emitted, t.doc, t.pos) for t in tr[b * max_new:b * max_new + int(n_steps[b])]]
+            res.append((out[b * max_new:b * max_new + int(n_out[b])].copy(), trace))
+        return res
 
     # -- inspection
     def enable_logits_dump(self, rows: int):

@@ -31,7 +31,7 @@ struct StepState {            // device pointers describing the rows of the step
     int *nacc, *next, *emit;             // results: [n_seqs], [n_seqs], [n_seqs][max_k+1]
     int *otok;                           // [R] arg max per row
 };
-struct GenState {             // device-resident state of llma_generate
+struct GenState {             // device-resident state of llma_generate, one per sequence of the batch
     int *y; int *n_out; int *n_steps; int *trace;  // y[max_new], trace[max_new][4]
     int *cur;                            // [2] (doc, pos) of the trigger of the step in flight
     const int *ref; const int *doc_offsets; const int *ref_doc; int ref_len, n_docs;
@@ -54,9 +54,9 @@ void launch_rope_kv_f32(const float *qkv, const StepState &s, const float *cs_ta
                         int R, int H, int dh, int max_seq, hipStream_t st);
 // final arg max over the per-row partials, then prefix accept + KV truncate + bookkeeping
 void launch_argmax_accept(const float *pval, const int *pidx, int n_part, const StepState &s, int n_seqs, int m,
-                          int max_k, const GenState *gen /*device copy or null*/, hipStream_t st);
-// trigger scan for the sequence being generated; fills keff[0] / draft[0][:]
-void launch_trigger(const GenState *gen_dev, const StepState &s, int max_k, hipStream_t st);
+                          int max_k, const GenState *gen /*device array [n_seqs] or null*/, hipStream_t st);
+// trigger scan for each sequence being generated (gen_dev[b]); fills keff[b] / draft[b][:]
+void launch_trigger(const GenState *gen_dev, const StepState &s, int n_seqs, int max_k, hipStream_t st);
 // stateless trigger on device arrays (llma_find_trigger): result[0..2] = matched, doc, pos
 void launch_trigger_plain(const int *y, int y_len, const int *ref, const int *doc_offsets, const int *ref_doc,
                           int ref_len, int n, int *result, hipStream_t st);

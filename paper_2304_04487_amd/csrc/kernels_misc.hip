@@ -121,7 +121,8 @@ __global__ __launch_bounds__(256) void argmax_accept_kernel(const float *__restr
     __shared__ int wi[4];
     __shared__ int o[40];
     const int b = blockIdx.x;
-    if (gen != nullptr && *gen->n_out >= gen->max_new) return;   // a step enqueued past the end: leave all state alone
+    if (gen != nullptr) gen += b;                                // llma_generate: one GenState per sequence of the batch
+    if (gen != nullptr && *gen->n_out >= gen->max_new) return;   // a finished sequence / a step enqueued past the end: leave all state alone
     const int keff = s.keff[b];
     for (int j = 0; j <= keff; ++j) {
         const size_t r = (size_t)b * m + j;
@@ -157,7 +158,7 @@ __global__ __launch_bounds__(256) void argmax_accept_kernel(const float *__restr
     for (int j = 0; j <= a; ++j) s.emit[b * (max_k + 1) + j] = o[j];
     s.T[slot] += a + 1;
     s.pending[slot] = o[a];
-    if (gen != nullptr && b == 0) {
+    if (gen != nullptr) {
         int i = *gen->n_out, st = *gen->n_steps;
         for (int j = 0; j <= a; ++j) gen->y[i + j] = o[j];
         gen->trace[st * 4 + 0] = 1 + keff;
@@ -213,7 +214,8 @@ __device__ __forceinline__ unsigned long long scan_reference(const int *y, int i
 }
 
 __global__ __launch_bounds__(256) void trigger_kernel(const GenState *gp, StepState s, int max_k) {
-    const GenState G = *gp;
+    const int b = blockIdx.x;                                    // one workgroup per sequence of the batch
+    const GenState G = gp[b];
     const int i = *G.n_out;
     unsigned long long best = 0ull;
     if (G.ref_len > 0 && G.k > 0 && i < G.max_new)
@@ -229,11 +231,11 @@ __global__ __launch_bounds__(256) void trigger_kernel(const GenState *gp, StepSt
         keff = keff < 0 ? 0 : keff;
         if (threadIdx.x == 0) { G.cur[0] = doc; G.cur[1] = p - G.doc_offsets[doc]; }
     }
-    if (threadIdx.x == 0) s.keff[0] = keff;
-    for (int j = threadIdx.x; j < keff; j += blockDim.x) s.draft[j] = G.ref[p + j];
+    if (threadIdx.x == 0) s.keff[b] = keff;
+    for (int j = threadIdx.x; j < keff; j += blockDim.x) s.draft[b * max_k + j] = G.ref[p + j];
 }
-void launch_trigger(const GenState *gen_dev, const StepState &s, int max_k, hipStream_t st) {
-    hipLaunchKernelGGL(trigger_kernel, dim3(1), dim3(256), 0, st, gen_dev, s, max_k);
+void launch_trigger(const GenState *gen_dev, const StepState &s, int n_seqs, int max_k, hipStream_t st) {
+    hipLaunchKernelGGL(trigger_kernel, dim3(n_seqs), dim3(256), 0, st, gen_dev, s, max_k);
 }
 
 __global__ __launch_bounds__(256) void trigger_plain_kernel(const int *y, int y_len, const int *ref, const int *doc_offsets,

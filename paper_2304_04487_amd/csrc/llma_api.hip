@@ -68,11 +68,11 @@ struct llma_ctx {
     int n_part = 0;
 
     StepState s{};
-    GenState gen{};               // host copy (device pointers inside)
     GenState *gen_dev = nullptr;
     int *gen_prompt = nullptr, *gen_ref = nullptr, *gen_doc_offsets = nullptr, *gen_ref_doc = nullptr;
-    int *gen_y = nullptr, *gen_trace = nullptr, *gen_counters = nullptr;   // counters: n_out, n_steps, cur[2], prefill base
-    int cap_prompt = 0, cap_ref = 0, cap_refdoc = 0, cap_docs = 0, cap_new = 0;
+    int *gen_y = nullptr, *gen_trace = nullptr;   // [sequence of the batch][max_new + 64] tokens, x 4 trace words
+    int *gen_counters = nullptr;                  // n_out[max_batch], n_steps[max_batch], cur[max_batch][2], prefill base
+    int cap_prompt = 0, cap_ref = 0, cap_refdoc = 0, cap_docs = 0, cap_y = 0, cap_trace = 0;
 
     std::vector<int> T_host, pending_host, import_mask_layers;
     float *logits_dump = nullptr;
@@ -278,13 +278,13 @@ static int create_impl(llma_ctx *c, const llma_weights *w) {
     HIP_TRY(c, hipMemsetAsync(s.keff, 0, g.max_batch * 4, c->st));
     HIP_TRY(c, hipMemsetAsync(s.row_pos, 0, Rp * 4, c->st));
     HIP_TRY(c, hipMemsetAsync(s.row_slot, 0, Rp * 4, c->st));
-    ALLOC(c, c->gen_dev, sizeof(GenState));
-    ALLOC(c, c->gen_counters, 8 * 4);
+    ALLOC(c, c->gen_dev, sizeof(GenState) * g.max_batch);
+    ALLOC(c, c->gen_counters, (size_t)(4 * g.max_batch + 4) * 4);
     c->T_host.assign(g.max_batch, 0);
     c->pending_host.assign(g.max_batch, -1);
     c->import_mask_layers.assign(g.max_batch, 0);
     HIP_TRY(c, hipStreamCreateWithFlags(&c->cap_st, hipStreamNonBlocking));
-    HIP_TRY(c, hipHostMalloc((void **)&c->pin_counts, 4 * sizeof(int), hipHostMallocDefault));
+    HIP_TRY(c, hipHostMalloc((void **)&c->pin_counts, (size_t)2 * g.max_batch * sizeof(int), hipHostMallocDefault));
     HIP_TRY(c, hipEventCreateWithFlags(&c->cnt_ev[0], hipEventDisableTiming));
     HIP_TRY(c, hipEventCreateWithFlags(&c->cnt_ev[1], hipEventDisableTiming));
     HIP_TRY(c, hipStreamSynchronize(c->st));
@@ -451,13 +451,13 @@ static int step_body(llma_ctx *c, int kind, int n_seqs, int m, int n_chunks, int
     hipStream_t st = c->run_st;
     const int mk = c->cfg.max_k;
     if (kind == STEP_PREFILL) {
-        launch_setup_prefill_rows(c->s, c->gen_prompt, c->gen_counters + 4, m, slot, c->cs_table, c->cfg.head_dim / 2, st);
+        launch_setup_prefill_rows(c->s, c->gen_prompt, c->gen_counters + 4 * c->cfg.max_batch, m, slot, c->cs_table, c->cfg.head_dim / 2, st);
         int rc = forward(c, 1, m, n_chunks, false, slot);
         if (rc) return rc;
         launch_advance_T(c->s, slot, m, st);
         return LLMA_OK;
     }
-    if (kind == STEP_GEN) launch_trigger(c->gen_dev, c->s, mk, st);
+    if (kind == STEP_GEN) launch_trigger(c->gen_dev, c->s, n_seqs, mk, st);
     launch_setup_step_rows(c->s, n_seqs, m, mk, c->cs_table, c->cfg.head_dim / 2, st);
     int rc = forward(c, n_seqs, m, n_chunks, true, slot);
     if (rc) return rc;
@@ -579,7 +579,7 @@ static int check_tokens(llma_ctx *c, const int32_t *t, int n, const char *who) {
 // feeds gen_prompt[0..n_feed) in chunks on top of the slot's cache; rows only write KV, no LM head
 static int prefill_rows(llma_ctx *c, int seq, int n_feed) {
     // the chunk's tokens are gen_prompt[T - base ..]: base = T at the start of the prompt
-    HIP_TRY(c, hipMemcpyAsync(c->gen_counters + 4, &c->T_host[seq], 4, hipMemcpyHostToDevice, c->st));
+    HIP_TRY(c, hipMemcpyAsync(c->gen_counters + 4 * c->cfg.max_batch, &c->T_host[seq], 4, hipMemcpyHostToDevice, c->st));
     HIP_TRY(c, hipStreamSynchronize(c->st));
     for (int off = 0; off < n_feed; off += c->Pmax) {
         const int m = n_feed - off < c->Pmax ? n_feed - off : c->Pmax;
@@ -715,76 +715,113 @@ extern "C" int llma_verify_step(llma_ctx *c, int32_t seq, const int32_t *draft, 
 // ------------------------------------------------------------------------------------------------
 // llma_generate (paper: Algorithm 1)
 // ------------------------------------------------------------------------------------------------
-extern "C" int llma_generate(llma_ctx *c, int32_t seq, const int32_t *prompt, int32_t prompt_len, const int32_t *ref,
-                             const int32_t *doc_offsets, int32_t n_docs, int32_t n, int32_t k, int32_t max_new,
-                             int32_t *out_tokens, int32_t *n_out, llma_step_rec *trace, int32_t *n_steps) {
-    int rc = check_slot(c, seq, "llma_generate");
-    if (rc) return rc;
+extern "C" int llma_generate_batch(llma_ctx *c, int32_t n_seqs, const int32_t *seqs, const int32_t *prompts,
+                                   const int32_t *prompt_offsets, const int32_t *refs, const int32_t *doc_offsets,
+                                   const int32_t *n_docs, int32_t n, int32_t k, int32_t max_new, int32_t *out_tokens,
+                                   int32_t *n_out, llma_step_rec *trace, int32_t *n_steps) {
+    if (!c) return fail(nullptr, LLMA_E_INVAL, "llma_generate: null context");
     const llma_model_cfg &g = c->cfg;
-    if (!prompt || prompt_len < 1 || !out_tokens || !n_out || max_new < 1) return fail(c, LLMA_E_INVAL, "llma_generate: null / empty argument");
+    if (!seqs || n_seqs < 1 || n_seqs > g.max_batch) return fail(c, LLMA_E_INVAL, "llma_generate: bad slot list (1..max_batch %d slots)", g.max_batch);
+    if (!prompts || !prompt_offsets || !out_tokens || !n_out || max_new < 1) return fail(c, LLMA_E_INVAL, "llma_generate: null / empty argument");
     if (n < 1) return fail(c, LLMA_E_INVAL, "llma_generate: n must be >= 1");
     if (k < 0 || k > g.max_k) return fail(c, LLMA_E_RANGE, "llma_generate: k %d outside [0, max_k %d]", k, g.max_k);
-    if (n_docs < 0 || (n_docs > 0 && !doc_offsets)) return fail(c, LLMA_E_INVAL, "llma_generate: bad documents");
-    int ref_len = 0;
-    if (n_docs > 0) {
-        if (doc_offsets[0] != 0) return fail(c, LLMA_E_INVAL, "llma_generate: doc_offsets[0] != 0");
-        for (int j = 0; j < n_docs; ++j)
-            if (doc_offsets[j + 1] < doc_offsets[j]) return fail(c, LLMA_E_INVAL, "llma_generate: doc_offsets decrease at %d", j);
-        ref_len = doc_offsets[n_docs];
-        if (ref_len > 0 && !ref) return fail(c, LLMA_E_INVAL, "llma_generate: null reference");
+    if (prompt_offsets[0] != 0) return fail(c, LLMA_E_INVAL, "llma_generate: prompt_offsets[0] != 0");
+    int rc;
+    // per sequence: where its reference tokens and its document list start in the concatenated inputs
+    std::vector<int> ref_start(n_seqs + 1, 0), docs_start(n_seqs + 1, 0);
+    int max_prompt = 0;
+    for (int b = 0; b < n_seqs; ++b) {
+        if ((rc = check_slot(c, seqs[b], "llma_generate"))) return rc;
+        for (int b2 = 0; b2 < b; ++b2)
+            if (seqs[b2] == seqs[b]) return fail(c, LLMA_E_INVAL, "llma_generate: slot %d listed twice", seqs[b]);
+        const int plen = prompt_offsets[b + 1] - prompt_offsets[b];
+        if (plen < 1) return fail(c, LLMA_E_INVAL, "llma_generate: sequence %d has an empty prompt", b);
+        if ((long)plen + max_new + k > g.max_seq)
+            return fail(c, LLMA_E_RANGE, "llma_generate: prompt %d + max_new %d + k %d > max_seq %d", plen, max_new, k, g.max_seq);
+        max_prompt = plen > max_prompt ? plen : max_prompt;
+        const int nd = n_docs ? n_docs[b] : 0;
+        if (nd < 0 || (nd > 0 && !doc_offsets)) return fail(c, LLMA_E_INVAL, "llma_generate: bad documents");
+        int rlen = 0;
+        if (nd > 0) {
+            const int32_t *dof = doc_offsets + docs_start[b];
+            if (dof[0] != 0) return fail(c, LLMA_E_INVAL, "llma_generate: doc_offsets[0] != 0");
+            for (int j = 0; j < nd; ++j)
+                if (dof[j + 1] < dof[j]) return fail(c, LLMA_E_INVAL, "llma_generate: doc_offsets decrease at %d", j);
+            rlen = dof[nd];
+            if (rlen > 0 && !refs) return fail(c, LLMA_E_INVAL, "llma_generate: null reference");
+        }
+        ref_start[b + 1] = ref_start[b] + rlen;
+        docs_start[b + 1] = docs_start[b] + (doc_offsets ? nd + 1 : 0);
     }
-    if ((long)prompt_len + max_new + k > g.max_seq)
-        return fail(c, LLMA_E_RANGE, "llma_generate: prompt %d + max_new %d + k %d > max_seq %d", prompt_len, max_new, k, g.max_seq);
-    if ((rc = check_tokens(c, prompt, prompt_len, "llma_generate(prompt)"))) return rc;
-    if (ref_len && (rc = check_tokens(c, ref, ref_len, "llma_generate(ref)"))) return rc;
-    if (c->logits_dump && k + 1 > c->dump_rows) return fail(c, LLMA_E_RANGE, "llma_generate: logits dump too small");
+    const int total_prompt = prompt_offsets[n_seqs], total_ref = ref_start[n_seqs];
+    if ((rc = check_tokens(c, prompts, total_prompt, "llma_generate(prompt)"))) return rc;
+    if (total_ref && (rc = check_tokens(c, refs, total_ref, "llma_generate(ref)"))) return rc;
+    if (c->logits_dump && n_seqs * (k + 1) > c->dump_rows) return fail(c, LLMA_E_RANGE, "llma_generate: logits dump too small");
 
     hipStream_t st = c->st;
-    if ((rc = ensure_cap(c, &c->gen_prompt, &c->cap_prompt, prompt_len))) return rc;
-    if ((rc = ensure_cap(c, &c->gen_ref, &c->cap_ref, ref_len))) return rc;
-    if ((rc = ensure_cap(c, &c->gen_ref_doc, &c->cap_refdoc, ref_len))) return rc;
-    if ((rc = ensure_cap(c, &c->gen_doc_offsets, &c->cap_docs, n_docs + 1))) return rc;
-    if (max_new > c->cap_new) {
-        int cy = 0, ct = 0;
-        if (c->gen_y) { HIP_TRY(c, hipStreamSynchronize(st)); dev_free_one(c, c->gen_y); dev_free_one(c, c->gen_trace); c->gen_y = c->gen_trace = nullptr; }
-        if ((rc = ensure_cap(c, &c->gen_y, &cy, max_new + 64))) return rc;
-        if ((rc = ensure_cap(c, &c->gen_trace, &ct, 4 * (max_new + 64)))) return rc;
-        c->cap_new = max_new;
+    const int ystride = max_new + 64;                       // per-sequence output / trace rows on the device
+    if ((rc = ensure_cap(c, &c->gen_prompt, &c->cap_prompt, max_prompt))) return rc;
+    if ((rc = ensure_cap(c, &c->gen_ref, &c->cap_ref, total_ref))) return rc;
+    if ((rc = ensure_cap(c, &c->gen_ref_doc, &c->cap_refdoc, total_ref))) return rc;
+    if ((rc = ensure_cap(c, &c->gen_doc_offsets, &c->cap_docs, docs_start[n_seqs] + n_seqs))) return rc;
+    if ((rc = ensure_cap(c, &c->gen_y, &c->cap_y, n_seqs * ystride))) return rc;
+    if ((rc = ensure_cap(c, &c->gen_trace, &c->cap_trace, 4 * n_seqs * ystride))) return rc;
+    if (total_ref) HIP_TRY(c, hipMemcpyAsync(c->gen_ref, refs, (size_t)total_ref * 4, hipMemcpyHostToDevice, st));
+    // device document lists: every sequence gets one (a sequence without reference: the single entry 0)
+    std::vector<int> dof_host, dof_at(n_seqs);
+    for (int b = 0; b < n_seqs; ++b) {
+        const int nd = n_docs ? n_docs[b] : 0;
+        dof_at[b] = (int)dof_host.size();
+        if (nd > 0) dof_host.insert(dof_host.end(), doc_offsets + docs_start[b], doc_offsets + docs_start[b] + nd + 1);
+        else dof_host.push_back(0);
     }
-    HIP_TRY(c, hipMemcpyAsync(c->gen_prompt, prompt, (size_t)prompt_len * 4, hipMemcpyHostToDevice, st));
-    if (ref_len) HIP_TRY(c, hipMemcpyAsync(c->gen_ref, ref, (size_t)ref_len * 4, hipMemcpyHostToDevice, st));
-    int zero_off = 0;
-    HIP_TRY(c, hipMemcpyAsync(c->gen_doc_offsets, n_docs > 0 ? doc_offsets : &zero_off, (size_t)(n_docs + 1) * 4, hipMemcpyHostToDevice, st));
-    launch_fill_ref_doc(c->gen_doc_offsets, n_docs, c->gen_ref_doc, ref_len, st);
-    HIP_TRY(c, hipMemsetAsync(c->gen_counters, 0, 16, st));
-    GenState &G = c->gen;
-    G.y = c->gen_y; G.n_out = c->gen_counters; G.n_steps = c->gen_counters + 1; G.cur = c->gen_counters + 2; G.trace = c->gen_trace;
-    G.ref = c->gen_ref; G.doc_offsets = c->gen_doc_offsets; G.ref_doc = c->gen_ref_doc; G.ref_len = ref_len; G.n_docs = n_docs;
-    G.n = n; G.k = k; G.max_new = max_new; G.prompt = c->gen_prompt;
-    HIP_TRY(c, hipMemcpyAsync(c->gen_dev, &G, sizeof(GenState), hipMemcpyHostToDevice, st));
-    HIP_TRY(c, hipStreamSynchronize(st));     // G and the host staging buffers may go out of scope / change
+    HIP_TRY(c, hipMemcpyAsync(c->gen_doc_offsets, dof_host.data(), dof_host.size() * 4, hipMemcpyHostToDevice, st));
+    HIP_TRY(c, hipMemsetAsync(c->gen_counters, 0, (size_t)(4 * g.max_batch + 4) * 4, st));
+    std::vector<GenState> G(n_seqs);
+    int *const cnt_out = c->gen_counters, *const cnt_steps = c->gen_counters + g.max_batch, *const cnt_cur = c->gen_counters + 2 * g.max_batch;
+    for (int b = 0; b < n_seqs; ++b) {
+        const int nd = n_docs ? n_docs[b] : 0, rlen = ref_start[b + 1] - ref_start[b];
+        if (rlen) launch_fill_ref_doc(c->gen_doc_offsets + dof_at[b], nd, c->gen_ref_doc + ref_start[b], rlen, st);
+        GenState &s = G[b];
+        s.y = c->gen_y + (size_t)b * ystride; s.trace = c->gen_trace + (size_t)4 * b * ystride;
+        s.n_out = cnt_out + b; s.n_steps = cnt_steps + b; s.cur = cnt_cur + 2 * b;
+        s.ref = c->gen_ref + ref_start[b]; s.doc_offsets = c->gen_doc_offsets + dof_at[b]; s.ref_doc = c->gen_ref_doc + ref_start[b];
+        s.ref_len = rlen; s.n_docs = nd; s.n = n; s.k = k; s.max_new = max_new; s.prompt = c->gen_prompt;
+    }
+    HIP_TRY(c, hipMemcpyAsync(c->gen_dev, G.data(), sizeof(GenState) * n_seqs, hipMemcpyHostToDevice, st));
+    HIP_TRY(c, hipStreamSynchronize(st));     // the host staging buffers may go out of scope / change
 
-    // ---- x: reset the slot, feed prompt[0..len-2], prompt[len-1] becomes the pending token
-    c->T_host[seq] = 0;
-    c->pending_host[seq] = prompt[prompt_len - 1];
-    c->import_mask_layers[seq] = 0;
-    if ((rc = push_state(c, seq))) return rc;
-    if ((rc = prefill_rows(c, seq, prompt_len - 1))) return rc;
+    // ---- x: reset each slot, feed prompt[0..len-2], prompt[len-1] becomes the pending token
+    std::vector<int> T0(n_seqs);
+    for (int b = 0; b < n_seqs; ++b) {
+        const int seq = seqs[b], plen = prompt_offsets[b + 1] - prompt_offsets[b];
+        const int32_t *prompt = prompts + prompt_offsets[b];
+        HIP_TRY(c, hipMemcpyAsync(c->gen_prompt, prompt, (size_t)plen * 4, hipMemcpyHostToDevice, st));
+        c->T_host[seq] = 0;
+        c->pending_host[seq] = prompt[plen - 1];
+        c->import_mask_layers[seq] = 0;
+        if ((rc = push_state(c, seq))) return rc;
+        if ((rc = prefill_rows(c, seq, plen - 1))) return rc;
+        HIP_TRY(c, hipStreamSynchronize(st));                   // gen_prompt is reused by the next sequence
+        T0[b] = c->T_host[seq];
+    }
 
-    // ---- the decoding loop: trigger -> rows -> forward -> accept, all on the device.  The host only
-    //      reads the output count back to know when to stop, and it does so one step late: step s+1
-    //      is already enqueued when the count of step s is awaited, so the GPU never waits for the
-    //      host.  The one step that may run after the last token is a no-op on the device (the
-    //      trigger copies nothing and the accept kernel leaves all state alone once max_new is reached).
+    // ---- the decoding loop: trigger -> rows -> forward -> accept, all on the device, all sequences of
+    //      the batch in one step (k + 1 rows each; a sequence that has its max_new tokens idles: its
+    //      trigger copies nothing and the accept kernel leaves its state alone).  The host only reads
+    //      the output counts back to know when to stop, and it does so one step late: step s+1 is
+    //      already enqueued when the counts of step s are awaited, so the GPU never waits for the host.
     const int m = k + 1;
-    HIP_TRY(c, hipMemcpyAsync(c->s.batch_slots, &seq, 4, hipMemcpyHostToDevice, st));
-    const int T0 = c->T_host[seq];
-    int produced = 0, steps = 0, enq = 0;
+    HIP_TRY(c, hipMemcpyAsync(c->s.batch_slots, seqs, (size_t)n_seqs * 4, hipMemcpyHostToDevice, st));
+    std::vector<int> produced(n_seqs, 0);
+    int steps = 0, enq = 0;
     auto enqueue = [&]() -> int {
         // cache length bound for the attention grid: every enqueued step adds at most m positions
-        int r = run_step(c, STEP_GEN, 1, m, T0 + produced + 2 * m, seq);
+        int t_max = 0;
+        for (int b = 0; b < n_seqs; ++b) t_max = T0[b] + produced[b] > t_max ? T0[b] + produced[b] : t_max;
+        int r = run_step(c, STEP_GEN, n_seqs, m, t_max + 2 * m, n_seqs == 1 ? seqs[0] : 0);
         if (r) return r;
-        HIP_TRY(c, hipMemcpyAsync(c->pin_counts + (enq & 1), G.n_out, 4, hipMemcpyDeviceToHost, st));
+        HIP_TRY(c, hipMemcpyAsync(c->pin_counts + (size_t)(enq & 1) * g.max_batch, cnt_out, (size_t)n_seqs * 4, hipMemcpyDeviceToHost, st));
         HIP_TRY(c, hipEventRecord(c->cnt_ev[enq & 1], st));
         ++enq;
         return LLMA_OK;
@@ -793,21 +830,42 @@ extern "C" int llma_generate(llma_ctx *c, int32_t seq, const int32_t *prompt, in
     while (true) {
         if ((rc = enqueue())) return rc;                        // one step ahead
         HIP_TRY(c, hipEventSynchronize(c->cnt_ev[steps & 1]));
-        const int now = c->pin_counts[steps & 1];
-        if (now <= produced || now > max_new) return fail(c, LLMA_E_HIP, "llma_generate: device output count went %d -> %d", produced, now);
-        produced = now;
+        bool done = true;
+        for (int b = 0; b < n_seqs; ++b) {
+            const int now = c->pin_counts[(size_t)(steps & 1) * g.max_batch + b];
+            if (now > max_new || now < produced[b] || (now == produced[b] && produced[b] < max_new))
+                return fail(c, LLMA_E_HIP, "llma_generate: device output count of sequence %d went %d -> %d", b, produced[b], now);
+            produced[b] = now;
+            done = done && now >= max_new;
+        }
         ++steps;
-        if (produced >= max_new) break;
+        if (done) break;
     }
     HIP_TRY(c, hipStreamSynchronize(st));                       // drains the step that ran ahead
-    c->T_host[seq] = T0 + produced;
-    HIP_TRY(c, hipMemcpyAsync(out_tokens, c->gen_y, (size_t)max_new * 4, hipMemcpyDeviceToHost, st));
-    if (trace) HIP_TRY(c, hipMemcpyAsync(trace, c->gen_trace, (size_t)steps * sizeof(llma_step_rec), hipMemcpyDeviceToHost, st));
-    HIP_TRY(c, hipMemcpyAsync(&c->pending_host[seq], c->s.pending + seq, 4, hipMemcpyDeviceToHost, st));
+    std::vector<int> nst(n_seqs);
+    HIP_TRY(c, hipMemcpyAsync(nst.data(), cnt_steps, (size_t)n_seqs * 4, hipMemcpyDeviceToHost, st));
     HIP_TRY(c, hipStreamSynchronize(st));
-    *n_out = produced;
-    if (n_steps) *n_steps = steps;
+    for (int b = 0; b < n_seqs; ++b) {
+        const int seq = seqs[b];
+        c->T_host[seq] = T0[b] + produced[b];
+        HIP_TRY(c, hipMemcpyAsync(out_tokens + (size_t)b * max_new, c->gen_y + (size_t)b * ystride, (size_t)max_new * 4, hipMemcpyDeviceToHost, st));
+        if (trace) HIP_TRY(c, hipMemcpyAsync(trace + (size_t)b * max_new, c->gen_trace + (size_t)4 * b * ystride, (size_t)nst[b] * sizeof(llma_step_rec), hipMemcpyDeviceToHost, st));
+        HIP_TRY(c, hipMemcpyAsync(&c->pending_host[seq], c->s.pending + seq, 4, hipMemcpyDeviceToHost, st));
+        n_out[b] = produced[b];
+        if (n_steps) n_steps[b] = nst[b];
+    }
+    HIP_TRY(c, hipStreamSynchronize(st));
     return LLMA_OK;
+}
+
+extern "C" int llma_generate(llma_ctx *c, int32_t seq, const int32_t *prompt, int32_t prompt_len, const int32_t *ref,
+                             const int32_t *doc_offsets, int32_t n_docs, int32_t n, int32_t k, int32_t max_new,
+                             int32_t *out_tokens, int32_t *n_out, llma_step_rec *trace, int32_t *n_steps) {
+    if (!c) return fail(nullptr, LLMA_E_INVAL, "llma_generate: null context");
+    if (prompt_len < 1) return fail(c, LLMA_E_INVAL, "llma_generate: null / empty argument");
+    if (n_docs < 0 || (n_docs > 0 && !doc_offsets)) return fail(c, LLMA_E_INVAL, "llma_generate: bad documents");
+    const int32_t poff[2] = {0, prompt_len};
+    return llma_generate_batch(c, 1, &seq, prompt, poff, ref, doc_offsets, &n_docs, n, k, max_new, out_tokens, n_out, trace, n_steps);
 }
 
 // ------------------------------------------------------------------------------------------------

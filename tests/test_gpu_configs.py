@@ -139,6 +139,57 @@ def test_cache_assisted_small_end_to_end(llma):
     ctx.close()
 
 
+# --------------------------------------------------------------------------- batched generation
+def test_batched_generate_small(llma):
+    """Three sequences decoded together (different prompt lengths, different references, one without
+    any): every sequence must come out exactly as the single-sequence call produces it -- tokens and
+    step trace -- and, where the oracle's greedy text has no near-tie, as the oracle's Algorithm 1."""
+    cfg = synth.SMALL
+    seed, max_new, n, k = 777, 48, 1, 6
+    w = synth.make_weights(cfg, seed)
+    om = OracleModel(cfg, w)
+    plens = (40, 23, 64)
+    prompts = [synth.uniform_tokens(seed, 300 + i, pl, cfg.vocab) for i, pl in enumerate(plens)]
+    cap = max(plens) + max_new + 40
+    ctx = llma.Context(cfg, w, max_seq=cap, max_batch=4, max_k=8)
+    singles0 = [ctx.generate(p, None, None, 1, 0, max_new, seq=0)[0] for p in prompts]
+    refs = []
+    for i, y in enumerate(singles0):
+        if i == 1:
+            refs.append(None)                                   # this sequence decodes plainly inside the batch
+            continue
+        r, _ = synth.make_ref(y, 0.6, 8.0, 96, cfg.vocab, seed + i)
+        refs.append((r, np.asarray([0, 40, 96], dtype=np.int32)))
+    singles = [ctx.generate(p, None if r is None else r[0], None if r is None else r[1], n, k, max_new, seq=0)
+               for p, r in zip(prompts, refs)]
+    batch = ctx.generate_batch(prompts, refs, n, k, max_new, seqs=[2, 0, 3])
+    for b in range(3):
+        assert np.array_equal(batch[b][0], singles[b][0]), f"sequence {b}: tokens differ from the single-sequence call"
+        assert batch[b][1] == singles[b][1], f"sequence {b}: step trace differs from the single-sequence call"
+        assert np.array_equal(batch[b][0], singles0[b]), f"sequence {b}: LLMA output differs from plain greedy"
+    assert batch[1][1] == [(1, 1, -1, -1)] * max_new
+    assert len(batch[0][1]) < max_new and len(batch[2][1]) < max_new
+    assert [ctx.get_state(s)[0] for s in (2, 0, 3)] == [pl - 1 + max_new for pl in plens]
+    # against the oracle, sequence by sequence (skipped for a sequence whose greedy text has a near-tie)
+    for b in (0, 2):
+        y = greedy_decode(CachedLLM(om, prompts[b], cap), max_new)
+        if not np.array_equal(np.asarray(y), singles0[b]):
+            print(f"  sequence {b}: GPU greedy text leaves the oracle's (near-tie); oracle comparison skipped")
+            continue
+        D = docs_from_flat(refs[b][0], refs[b][1])
+        yo, trace = llma_decode(CachedLLM(om, prompts[b], cap), D, n, k, max_new)
+        assert yo == y and batch[b][1] == trace, f"sequence {b}: step trace differs from the oracle's"
+    # error paths leave the context usable
+    with pytest.raises(llma.LlmaError):
+        ctx.generate_batch(prompts[:2], refs[:2], n, k, max_new, seqs=[1, 1])
+    with pytest.raises(llma.LlmaError):
+        ctx.generate_batch(prompts + prompts, refs + refs, n, k, max_new)
+    again = ctx.generate_batch(prompts, refs, n, k, max_new)
+    assert all(np.array_equal(again[b][0], singles[b][0]) for b in range(3))
+    print(f"batched generate: steps per sequence {[len(t) for _, t in batch]} for {max_new} tokens each")
+    ctx.close()
+
+
 # --------------------------------------------------------------------------- 7B shape, full depth
 @pytest.mark.timeout(600)
 def test_7b_shape_verify_step_logits(llma):
