@@ -17,13 +17,6 @@
 #include "common.h"
 #include "kernels.h"
 
-#define PANEL_PICK_RT(a, b, c) a
-#define PANEL_PICK_FT(a, b, c) b
-#define PANEL_PICK_WV(a, b, c) c
-#define PANEL_CFG_RT(cfg) PANEL_PICK_RT(cfg)
-#define PANEL_CFG_FT(cfg) PANEL_PICK_FT(cfg)
-#define PANEL_CFG_WV(cfg) PANEL_PICK_WV(cfg)
-
 // =============================================================================================
 // weight re-tiling: row-major [N][K] bf16 -> 1 KiB MFMA A-operand blocks (see common.h)
 // =============================================================================================
@@ -676,17 +669,32 @@ static void launch_panel_cfg(const GemmArgs &a, hipStream_t st) {
     hipLaunchKernelGGL((gemm_panel_bf16<RT, EPI, FT, WV>), grid, block, lds, st, a2);
 }
 
-// prompt-processing GEMM over any number of rows (needs a.rstd_in for the norm-scaled epilogues)
-#ifndef PANEL_CFG
-#define PANEL_CFG 8, 2, 8      /* row tiles, weight tiles per wave, waves */
-#define PANEL_CFG_GU 8, 1, 8
-#endif
+// prompt-processing GEMM over any number of rows (needs a.rstd_in for the norm-scaled epilogues).
+// A workgroup owns 8 waves x FT feature tiles (FT = 2; SwiGLU: one gate/up pair) and RT row tiles,
+// RT = 8 or 6: one workgroup fits a compute unit, so the launch runs in rounds of n_cu workgroups and
+// the row-block height that needs the least rounds x height wins (1535 rows on 256 units: 6, where
+// QKV is 3.0 rounds instead of 2.25 and O / down exactly 1.0 instead of 0.75).
+template <int EPI, int FT>
+static void launch_panel_epi(const GemmArgs &a, hipStream_t st) {
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n_cu = prop.multiProcessorCount;
+        if (n_cu <= 0) n_cu = 256;
+    }
+    const int fb = ((a.plan.tasks + 8 * FT - 1) / (8 * FT) + 7) / 8 * 8;
+    const int row_tiles = (a.rows + 15) / 16;
+    auto cost = [&](int rt) { return (long)((fb * ((row_tiles + rt - 1) / rt) + n_cu - 1) / n_cu) * rt; };
+    if (cost(6) < cost(8)) launch_panel_cfg<6, EPI, FT, 8>(a, st);
+    else launch_panel_cfg<8, EPI, FT, 8>(a, st);
+}
 void launch_gemm_panel_bf16(const GemmArgs &a, hipStream_t st) {
     switch (a.epi) {
-        case EPI_RESID: launch_panel_cfg<PANEL_CFG_RT(PANEL_CFG), EPI_RESID, PANEL_CFG_FT(PANEL_CFG), PANEL_CFG_WV(PANEL_CFG)>(a, st); break;
-        case EPI_SWIGLU: launch_panel_cfg<PANEL_CFG_RT(PANEL_CFG_GU), EPI_SWIGLU, PANEL_CFG_FT(PANEL_CFG_GU), PANEL_CFG_WV(PANEL_CFG_GU)>(a, st); break;
-        case EPI_QKV: launch_panel_cfg<PANEL_CFG_RT(PANEL_CFG), EPI_QKV, PANEL_CFG_FT(PANEL_CFG), PANEL_CFG_WV(PANEL_CFG)>(a, st); break;
-        default: launch_panel_cfg<PANEL_CFG_RT(PANEL_CFG), EPI_LMHEAD, PANEL_CFG_FT(PANEL_CFG), PANEL_CFG_WV(PANEL_CFG)>(a, st); break;
+        case EPI_RESID: launch_panel_epi<EPI_RESID, 2>(a, st); break;
+        case EPI_SWIGLU: launch_panel_epi<EPI_SWIGLU, 1>(a, st); break;
+        case EPI_QKV: launch_panel_epi<EPI_QKV, 2>(a, st); break;
+        default: launch_panel_epi<EPI_LMHEAD, 2>(a, st); break;
     }
 }
 
