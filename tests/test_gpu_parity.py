@@ -238,6 +238,44 @@ def test_tiny_config_end_to_end(llma):
     ctx.close()
 
 
+def test_generate_degenerate_cases(llma):
+    """The method's edge cases on the tiny fp32 model, tokens and step traces against the oracle:
+    one-token prompt (nothing to prefill), one new token, n longer than anything generated so far,
+    a reference shorter than n, a match in the last position of a document (no draft left), drafts
+    cut by the end of a document and by the token budget, k at the context's maximum, a reference
+    equal to the whole output (every draft accepted), many one-token documents."""
+    cfg = synth.TINY
+    w = synth.make_weights(cfg, 5)
+    om = OracleModel(cfg, w)
+    ctx = llma.Context(cfg, w, max_seq=96, max_batch=1, max_k=16)
+
+    def both(prompt, docs, n, k, max_new):
+        flat = np.asarray([t for d in docs for t in d], dtype=np.int32)
+        offs = np.concatenate([[0], np.cumsum([len(d) for d in docs])]).astype(np.int32)
+        yo, to = llma_decode(CachedLLM(om, prompt, 96), docs, n, k, max_new)
+        assert yo == greedy_decode(CachedLLM(om, prompt, 96), max_new)
+        g, t = ctx.generate(prompt, flat, offs, n, k, max_new)
+        assert g.tolist() == yo and t == to, (len(prompt), [len(d) for d in docs], n, k, max_new, t, to)
+        return yo, to
+
+    prompt = synth.uniform_tokens(5, 1, 12, cfg.vocab).tolist()
+    y = greedy_decode(CachedLLM(om, prompt, 96), 40)
+    both([7], [y[:10]], 1, 4, 20)                                  # one-token prompt
+    both(prompt, [y], 1, 8, 1)                                     # a single new token
+    _, t = both(prompt, [y], 6, 4, 40)                             # no trigger before 6 tokens exist
+    assert all(r == (1, 1, -1, -1) for r in t[:6])
+    both(prompt, [y[:2]], 3, 4, 16)                                # reference shorter than n: never matches
+    _, t = both(prompt, [y[:5], y[20:30]], 1, 8, 40)               # match at a document's last token, drafts cut by its end
+    assert any(rows == 1 and doc >= 0 for rows, _, doc, _ in t) or any(1 < rows < 9 for rows, _, _, _ in t)
+    _, t = both(prompt, [y], 1, 16, 40)                            # k = max_k, reference = output: long accepted runs
+    assert max(e for _, e, _, _ in t) == 17 and t[-1][0] <= 17
+    _, t = both(prompt, [y], 2, 16, 37)                            # the token budget cuts the last draft
+    assert sum(e for _, e, _, _ in t) == 37
+    both(prompt, [[tok] for tok in y[:24]], 1, 4, 30)              # 24 one-token documents: matches but nothing to copy
+    both(prompt, [[], y[3:9], []], 1, 4, 20)                       # empty documents among real ones
+    ctx.close()
+
+
 def test_argument_errors_leave_context_unchanged(llma):
     cfg = synth.TINY
     w = synth.make_weights(cfg, 1)
