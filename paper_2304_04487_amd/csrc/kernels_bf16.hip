@@ -980,10 +980,176 @@ __global__ void attn_combine_bf16_kernel(AttnArgs a, int rq) {
     *(u32x2 *)((bf16_t *)a.out_lo + o) = lo;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Prompt-pass attention (more than 48 rows of one sequence): a workgroup owns 32 query rows of one
+// head and walks over all 128-position chunks its rows can see; wave w takes positions
+// 32 w .. 32 w + 31 of every chunk and keeps its own running (max, sum, O) over them (online
+// softmax, no synchronisation inside the walk), the next chunk's K/V blocks are requested while the
+// current one is multiplied; at the end the four waves merge through LDS in wave order and the
+// normalised rows go straight to the hi/lo planes -- no partials, no combine kernel.  Row blocks
+// are numbered from the end of the prompt (longest walks start first).
+// ---------------------------------------------------------------------------------------------
+template <int DH, bool KVS>
+__global__ __launch_bounds__(256) void attn_prompt_bf16_kernel(AttnArgs a) {
+    constexpr int KSTEPS = DH / 32, DT = DH / 16, NTQ = 2, RQ = NTQ * 16;
+    __shared__ float sm[4][RQ], sl[4][RQ];
+    __shared__ float so[4][RQ][DH + 4];
+    const int rb = gridDim.x - 1 - blockIdx.x, h = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 15, g = lane >> 4;
+    const int slot = a.slot_const;
+    const int m = a.m, j0 = rb * RQ;
+    const int m_blk = (m - j0 < RQ) ? m - j0 : RQ;
+    const int d_model = a.H * DH;
+    const size_t head_base = ((size_t)slot * a.H + h) * (size_t)a.max_seq * DH;
+    const bf16_t *kh = (const bf16_t *)a.Khi + head_base, *kl = (const bf16_t *)a.Klo + head_base;
+    const bf16_t *vh = (const bf16_t *)a.Vhi + head_base, *vl = (const bf16_t *)a.Vlo + head_base;
+    const int T = a.T[slot];
+    const int kv_len = T + j0 + m_blk;                  // positions the block's last row can see
+    const int n_ch = (kv_len + ATTN_CHUNK - 1) / ATTN_CHUNK;
+
+    u32x4 qh[NTQ][KSTEPS], ql[NTQ][KSTEPS];
+    int rpos[NTQ];
+#pragma unroll
+    for (int q = 0; q < NTQ; ++q) {
+        const int j = j0 + q * 16 + n;
+        rpos[q] = j < m ? T + j : -1;
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s) {
+            const size_t off = xtile_off(j < m ? j : 0, h * DH + s * 32 + g * 8, d_model / 32);
+            qh[q][s] = *(const u32x4 *)((const bf16_t *)a.Qhi + off);
+            ql[q][s] = *(const u32x4 *)((const bf16_t *)a.Qlo + off);
+        }
+    }
+    auto fetch = [&](int c, u32x4 (&ka)[2][KSTEPS], u32x4 (&kb)[2][KSTEPS], u32x4 (&va)[DT], u32x4 (&vb)[DT]) {
+        const int key0 = c * ATTN_CHUNK + wave * 32;    // below the rounded capacity for every launched chunk
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int s = 0; s < KSTEPS; ++s) {
+                const size_t off = (size_t)(key0 / 16 + t) * (16 * DH) + s * 512 + lane * 8;
+                ka[t][s] = *(const u32x4 *)(kh + off);
+                if (KVS) kb[t][s] = *(const u32x4 *)(kl + off);
+            }
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            const size_t off = (size_t)(key0 / 32) * (32 * DH) + dt * 512 + lane * 8;
+            va[dt] = *(const u32x4 *)(vh + off);
+            if (KVS) vb[dt] = *(const u32x4 *)(vl + off);
+        }
+    };
+    float mrow[NTQ], lrow[NTQ];
+    f32x4 o[NTQ][DT];
+#pragma unroll
+    for (int q = 0; q < NTQ; ++q) {
+        mrow[q] = LLMA_NEG_INF;
+        lrow[q] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) o[q][dt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
+    auto consume = [&](int c, u32x4 (&ka)[2][KSTEPS], u32x4 (&kb)[2][KSTEPS], u32x4 (&va)[DT], u32x4 (&vb)[DT]) {
+        const int key0 = c * ATTN_CHUNK + wave * 32;
+        if (key0 >= kv_len) return;                     // uniform for the wave
+#pragma unroll
+        for (int q = 0; q < NTQ; ++q) {
+            float sv[8];
+            float mx = LLMA_NEG_INF;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s = 0; s < KSTEPS; ++s) {
+                    acc = mfma16x16x32(ka[t][s], qh[q][s], acc);
+                    acc = mfma16x16x32(ka[t][s], ql[q][s], acc);
+                    if (KVS) acc = mfma16x16x32(kb[t][s], qh[q][s], acc);
+                }
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int key = key0 + t * 16 + 4 * g + r4;
+                    float v = acc[r4] * a.scale;
+                    v = (key > rpos[q]) ? LLMA_NEG_INF : v;
+                    sv[t * 4 + r4] = v;
+                    mx = fmaxf(mx, v);
+                }
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(mrow[q], mx);
+            const float alpha = (mrow[q] == LLMA_NEG_INF) ? 0.f : __expf(mrow[q] - m_new);   // m_new finite then
+            float psum = 0.f;
+            float p[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                p[i] = (m_new == LLMA_NEG_INF) ? 0.f : __expf(sv[i] - m_new);
+                psum += p[i];
+            }
+            lrow[q] = lrow[q] * alpha + psum;           // this lane's 8 keys; lanes are added at the end
+            mrow[q] = m_new;
+            u32x2 h0, l0, h1, l1;
+            split4(p, h0, l0);
+            split4(p + 4, h1, l1);
+            const u32x4 ph = (u32x4){h0[0], h0[1], h1[0], h1[1]};
+            const u32x4 pl = (u32x4){l0[0], l0[1], l1[0], l1[1]};
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                o[q][dt] *= alpha;
+                o[q][dt] = mfma16x16x32(va[dt], ph, o[q][dt]);
+                o[q][dt] = mfma16x16x32(va[dt], pl, o[q][dt]);
+                if (KVS) o[q][dt] = mfma16x16x32(vb[dt], ph, o[q][dt]);
+            }
+        }
+    };
+    u32x4 kaA[2][KSTEPS], kbA[2][KSTEPS], vaA[DT], vbA[DT], kaB[2][KSTEPS], kbB[2][KSTEPS], vaB[DT], vbB[DT];
+    fetch(0, kaA, kbA, vaA, vbA);
+    for (int c = 0; c < n_ch; c += 2) {
+        if (c + 1 < n_ch) fetch(c + 1, kaB, kbB, vaB, vbB);
+        consume(c, kaA, kbA, vaA, vbA);
+        if (c + 1 >= n_ch) break;
+        if (c + 2 < n_ch) fetch(c + 2, kaA, kbA, vaA, vbA);
+        consume(c + 1, kaB, kbB, vaB, vbB);
+    }
+    // ---- merge the four waves in wave order, normalise, write the hi/lo planes
+#pragma unroll
+    for (int q = 0; q < NTQ; ++q) {
+        float l = lrow[q];
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        if (g == 0) { sm[wave][q * 16 + n] = mrow[q]; sl[wave][q * 16 + n] = l; }
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) *(f32x4 *)&so[wave][q * 16 + n][dt * 16 + 4 * g] = o[q][dt];
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < m_blk * (DH / 4); idx += 256) {
+        const int j = idx / (DH / 4), d4 = idx % (DH / 4);
+        float M = LLMA_NEG_INF;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) M = fmaxf(M, sm[w][j]);
+        f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+        float L = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float mw = sm[w][j];
+            const float sc = (mw == LLMA_NEG_INF) ? 0.f : __expf(mw - M);
+            acc += *(const f32x4 *)&so[w][j][d4 * 4] * sc;
+            L += sl[w][j] * sc;
+        }
+        float v[4] = {acc[0] / L, acc[1] / L, acc[2] / L, acc[3] / L};
+        u32x2 hi, lo;
+        split4(v, hi, lo);
+        const size_t off = xtile_off(j0 + j, h * DH + d4 * 4, a.out_KSp);
+        *(u32x2 *)((bf16_t *)a.out_hi + off) = hi;
+        *(u32x2 *)((bf16_t *)a.out_lo + off) = lo;
+    }
+}
+
 template <int DH, bool KVS>
 static void launch_attn_dh(const AttnArgs &a0, hipStream_t st) {
     // up to 48 rows per workgroup; longer row lists (prompt processing) are cut into row blocks
     AttnArgs a = a0;
+    if (a.n_seqs == 1 && a.m > 48 && a.slot_const >= 0) {           // prompt pass
+        hipLaunchKernelGGL((attn_prompt_bf16_kernel<DH, KVS>), dim3((a.m + 31) / 32, a.H), dim3(256), 0, st, a);
+        return;
+    }
     const int ntq = a.m > 32 ? 3 : (a.m + 15) / 16;
     a.n_rblocks = (a.m + ntq * 16 - 1) / (ntq * 16);
     dim3 grid(a.n_chunks, a.H, a.n_seqs * a.n_rblocks);

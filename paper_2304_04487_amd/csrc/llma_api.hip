@@ -239,11 +239,9 @@ static int create_impl(llma_ctx *c, const llma_weights *w) {
         if ((rc = zalloc((void **)&c->ssq, Rp * (d / 16) * 4))) return rc;
         if ((rc = zalloc((void **)&c->rstd, Rp * 4))) return rc;
         c->nc_max = c->seq_cap / ATTN_CHUNK;
-        // attention partials: [sequences][heads][chunks][rows]: 48 rows per sequence in decoding steps,
-        // the whole prompt pass (one sequence) in prompt processing
-        size_t np = (size_t)g.max_batch * H * c->nc_max * 48;
-        const size_t np_prompt = (size_t)H * c->nc_max * (((size_t)c->Pmax + 47) / 48 * 48);
-        if (np_prompt > np) np = np_prompt;
+        // attention partials: [sequences][heads][chunks][rows], up to 48 rows per sequence (longer
+        // prompt passes run the walking kernel, which has no partials)
+        const size_t np = (size_t)g.max_batch * H * c->nc_max * 48;
         ALLOC(c, c->po, np * dh * 4);
         ALLOC(c, c->pm, np * 4);
         ALLOC(c, c->pl, np * 4);
