@@ -83,7 +83,7 @@ struct GemmPlan {
     int KSp;         // k-steps (of 32) per feature tile
     int tasks;       // feature tiles (SWIGLU: gate/up tile pairs)
     int tk_ft;       // tile-K kernel: feature tiles per workgroup
-    int tk_waves;    //   and waves per workgroup
+    int tk_waves;    //   and K slices (= waves, or half as many waves taking two slices each)
 };
 
 struct GemmArgs {          // bf16 path (fields marked f32 are used by the fp32 kernels only)

@@ -302,11 +302,7 @@ __global__ __launch_bounds__((TileKShape<NT, FT>::MAX_THREADS)) void gemm_tilek_
     constexpr int SL = TileKShape<NT, FT>::SL;
     constexpr int TILES = (EPI == EPI_SWIGLU) ? 2 : 1;
     constexpr int AT = FT * TILES;                 // weight tiles per k-step
-#ifndef TK_UB_SMALL
-#define TK_UB_SMALL 2
-#define TK_UB_BIG 1
-#endif
-    constexpr int UB = (AT * NT >= 4) ? TK_UB_BIG : TK_UB_SMALL;     // k-steps per load batch
+    constexpr int UB = (AT * NT >= 4) ? 1 : 2;     // k-steps per load batch
     constexpr int PL = SPLIT ? 2 : 1;
     extern __shared__ f32x4 red[];                 // [S][AT][NT][64], then rstd[16*NT] floats
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, S = (blockDim.x >> 6) * SL;
@@ -456,18 +452,8 @@ static void launch_tilek(const GemmArgs &a, hipStream_t st) {
 
 template <int NT, int EPI>
 static void launch_gemm_nt_epi(const GemmArgs &a, hipStream_t st) {
-    constexpr int TILES = (EPI == EPI_SWIGLU) ? 2 : 1;
-    const GemmPlan &p = a.plan;
-    if (TILES == 2) {
-        if (p.tk_ft == 1) launch_tilek<NT, EPI, 1>(a, st);
-        else if (p.tk_ft == 2) launch_tilek<NT, EPI, 2>(a, st);
-        else launch_tilek<NT, EPI, 3>(a, st);
-    } else {
-        if (p.tk_ft == 1) launch_tilek<NT, EPI, 1>(a, st);
-        else if (p.tk_ft == 2) launch_tilek<NT, EPI, 2>(a, st);
-        else if (p.tk_ft == 3) launch_tilek<NT, EPI, 3>(a, st);
-        else launch_tilek<NT, EPI, 4>(a, st);
-    }
+    if (a.plan.tk_ft == 1) launch_tilek<NT, EPI, 1>(a, st);
+    else launch_tilek<NT, EPI, 3>(a, st);               // make_gemm_plan() knows 1 and 3 only
 }
 
 template <int NT>
@@ -723,9 +709,9 @@ void launch_gemm_bf16(const GemmArgs &a0, hipStream_t st) {
     }
 }
 
-// how a [N][K] weight matrix is cut into work for the tile-K kernel: tiles per workgroup so that the
-// grid is about one to three workgroups per compute unit, 16 waves when a workgroup owns several
-// tiles, else 8 (measured best on the 7B shapes; LLMA_GEMM_TK / LLMA_GEMM_TKW override for experiments)
+// how a [N][K] weight matrix is cut into work for the tile-K kernel: three feature tiles per
+// workgroup and 16 K slices for matrices of 640+ tiles (QKV, LM head), else one tile (pair) and 8
+// slices -- the combinations measured fastest on the 7B and 13B shapes
 GemmPlan make_gemm_plan(int N, int K, int tiles_per_task) {
     GemmPlan p;
     p.N = N; p.K = K;
@@ -734,7 +720,6 @@ GemmPlan make_gemm_plan(int N, int K, int tiles_per_task) {
     // (waves x tiles per workgroup <= 48 keeps the wave-order reduction of three row tiles inside LDS)
     p.tk_ft = (tiles_per_task == 2) ? 1 : (p.tasks >= 640 ? 3 : 1);
     p.tk_waves = p.tk_ft > 1 ? 16 : 8;
-    { const char *e = getenv("LLMA_GEMM_TK"); if (e) p.tk_ft = atoi(e); const char *w = getenv("LLMA_GEMM_TKW"); if (w) p.tk_waves = atoi(w); }
     return p;
 }
 
