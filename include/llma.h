@@ -170,7 +170,9 @@ int llma_generate(llma_ctx *ctx, int32_t seq, const int32_t *prompt, int32_t pro
  *   trace           n_seqs * max_new records, row b = sequence b (may be NULL); n_steps
  *                   int32[n_seqs] (may be NULL)
  * Needs n_seqs <= max_batch and prompt length + max_new + k <= max_seq for every sequence.
- * The tokens of a sequence are those the single-sequence call produces for it.
+ * The tokens of a sequence are those the single-sequence call produces for it (bit for bit
+ * while n_seqs * (k + 1) <= 48; larger steps run a different GEMM whose sums are taken in
+ * another order, so a near-tie of two logits may then resolve differently).
  * Errors: INVAL, RANGE; on error before the first launch the context is unchanged. */
 int llma_generate_batch(llma_ctx *ctx, int32_t n_seqs, const int32_t *seqs,
                         const int32_t *prompts, const int32_t *prompt_offsets,

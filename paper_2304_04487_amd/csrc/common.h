@@ -84,6 +84,7 @@ struct GemmPlan {
     int tasks;       // feature tiles (SWIGLU: gate/up tile pairs)
     int tk_ft;       // tile-K kernel: feature tiles per workgroup
     int tk_waves;    //   and K slices (= waves, or half as many waves taking two slices each)
+    int n_split;     // panel kernel, batched steps: ranges the K axis is cut into (1 = no split)
 };
 
 struct GemmArgs {          // bf16 path (fields marked f32 are used by the fp32 kernels only)
@@ -101,6 +102,8 @@ struct GemmArgs {          // bf16 path (fields marked f32 are used by the fp32 
     float eps;
     const float *rstd_in;  // panel GEMM only: [rows] precomputed rstd (instead of ssq_in)
     int panel_rb;          // panel GEMM only: row blocks (set by the launcher)
+    int ksplit;            // panel GEMM only: > 1 = the K axis is cut into this many ranges of k-chunks, partial sums via `part`
+    float *part;           //   [ksplit][tiles][row tiles][64 lanes x 4] fp32 partial sums (register images)
     // EPI_STORE (f32) / EPI_RESID / EPI_LMHEAD
     float *out;            // STORE: [rows][N]; RESID: h[rows][N] += ; LMHEAD: optional logits dump (may be null)
     // EPI_RESID: prepares the next RMSNorm'd GEMM input

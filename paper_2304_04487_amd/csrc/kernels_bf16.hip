@@ -564,16 +564,21 @@ __global__ __launch_bounds__(WV * 64) void gemm_panel_bf16(GemmArgs a0) {
 #pragma unroll
         for (int t = 0; t < RT; ++t) acc[i][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    const int NC = (KSp + KC - 1) / KC;
+    // split-K form (batched decoding steps, too few rows to fill the chip otherwise): blockIdx.y picks
+    // one of a0.ksplit contiguous ranges of k-chunks; the raw sums go to a0.part and a second kernel
+    // adds the ranges in order and runs the epilogue
+    const int n_split = a0.ksplit > 1 ? a0.ksplit : 1;
+    const int NC_all = (KSp + KC - 1) / KC;
+    const int kc_lo = (int)((long)NC_all * blockIdx.y / n_split), NC = (int)((long)NC_all * (blockIdx.y + 1) / n_split);
     u32x4 xv[PER], avA[AT][KC], avB[AT][KC];
-    fetch_x(0, xv);
-    fetch_w(0, avA);
+    fetch_x(kc_lo, xv);
+    fetch_w(kc_lo, avA);
     if (EPI != EPI_RESID)
         for (int r = threadIdx.x; r < 16 * RT; r += NTHR) rstd_s[r] = (r < a.rows) ? a.rstd_in[r0 + r] : 0.f;
     stash_x(0, xv);
     __syncthreads();
-    for (int kc = 0; kc < NC; ++kc) {
-        const int buf = kc & 1;
+    for (int kc = kc_lo; kc < NC; ++kc) {
+        const int buf = (kc - kc_lo) & 1;
         if (kc + 1 < NC) fetch_x(kc + 1, xv);
         auto step = [&](u32x4 (&av)[AT][KC], u32x4 (&avn)[AT][KC]) {
             if (kc + 1 < NC) fetch_w(kc + 1, avn);
@@ -598,6 +603,19 @@ __global__ __launch_bounds__(WV * 64) void gemm_panel_bf16(GemmArgs a0) {
         __syncthreads();
     }
 
+    if (n_split > 1) {
+        // partial sums as register images: [range][tile (SwiGLU: gate tiles, then up tiles)][row tile][lane]
+        f32x4 *part = (f32x4 *)a0.part;
+#pragma unroll
+        for (int f = 0; f < FT; ++f)
+#pragma unroll
+            for (int i = 0; i < TILES; ++i)
+#pragma unroll
+                for (int t = 0; t < RT; ++t)
+                    if (task0 + f < p.tasks && rt0 + t < n_rt_total)
+                        part[(((size_t)blockIdx.y * (p.tasks * TILES) + task0 + f + i * p.tasks) * n_rt_total + rt0 + t) * 64 + lane] = acc[f * TILES + i][t];
+        return;
+    }
     // ---- epilogues, one feature tile (pair) at a time
 #pragma unroll
     for (int f = 0; f < FT; ++f) {
@@ -642,6 +660,40 @@ void launch_rstd_rows(const float *ssq, int ssq_tiles, float eps, float *rstd, i
     hipLaunchKernelGGL(rstd_rows_kernel, dim3((rows + 15) / 16), dim3(256), 0, st, ssq, ssq_tiles, eps, rstd, rows);
 }
 
+// second half of the split-K form: one wave per (feature tile (pair), row tile) adds the ranges'
+// partial sums in range order and runs the fused epilogue on the result
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_splitk_finish_bf16(GemmArgs a0) {
+    constexpr int TILES = (EPI == EPI_SWIGLU) ? 2 : 1;
+    __shared__ float rstd_sh[4][16];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const GemmPlan &p = a0.plan;
+    const int n_rt = (a0.rows + 15) / 16;
+    const int unit = blockIdx.x * 4 + wave;
+    if (unit >= p.tasks * n_rt) return;                         // (no workgroup barrier below)
+    const int task = unit / n_rt, t = unit % n_rt;
+    GemmArgs a = a0;
+    offset_rows(a, p, t * 16);
+    EpiIn<1> in;
+    epi_prefetch<1, EPI>(a, p, task, lane, in);
+    if (EPI != EPI_RESID && lane < 16) rstd_sh[wave][lane] = (lane < a.rows) ? a0.rstd_in[t * 16 + lane] : 0.f;
+    const f32x4 *part = (const f32x4 *)a0.part;
+    f32x4 sum[TILES][1];
+#pragma unroll
+    for (int i = 0; i < TILES; ++i) {
+        const size_t tile = (size_t)(task + i * p.tasks) * n_rt + t, stride = (size_t)p.tasks * TILES * n_rt;
+        f32x4 v = part[tile * 64 + lane];
+        for (int s = 1; s < a0.ksplit; ++s) v += part[(s * stride + tile) * 64 + lane];
+        sum[i][0] = v;
+    }
+    gemm_epilogue<1, EPI, TILES>(a, p, task, lane, sum, rstd_sh[wave], in);
+}
+template <int EPI>
+static void launch_splitk_finish(const GemmArgs &a, hipStream_t st) {
+    const int units = a.plan.tasks * ((a.rows + 15) / 16);
+    hipLaunchKernelGGL((gemm_splitk_finish_bf16<EPI>), dim3((units + 3) / 4), dim3(256), 0, st, a);
+}
+
 template <int RT, int EPI, int FT, int WV>
 static void launch_panel_cfg(const GemmArgs &a, hipStream_t st) {
     const GemmPlan &p = a.plan;
@@ -649,7 +701,7 @@ static void launch_panel_cfg(const GemmArgs &a, hipStream_t st) {
     const int FB = ((p.tasks + WV * FT - 1) / (WV * FT) + 7) / 8 * 8;    // feature blocks, padded to whole groups of 8
     GemmArgs a2 = a;
     a2.panel_rb = (a.rows + 16 * RT - 1) / (16 * RT);
-    dim3 grid(FB * a2.panel_rb), block(WV * 64);
+    dim3 grid(FB * a2.panel_rb, a.ksplit > 1 ? a.ksplit : 1), block(WV * 64);
     static bool attr_done = false;
     if (!attr_done) { (void)hipFuncSetAttribute((const void *)gemm_panel_bf16<RT, EPI, FT, WV>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); attr_done = true; }
     hipLaunchKernelGGL((gemm_panel_bf16<RT, EPI, FT, WV>), grid, block, lds, st, a2);
@@ -657,7 +709,7 @@ static void launch_panel_cfg(const GemmArgs &a, hipStream_t st) {
 
 // prompt-processing GEMM over any number of rows (needs a.rstd_in for the norm-scaled epilogues).
 // A workgroup owns 8 waves x FT feature tiles (FT = 2; SwiGLU: one gate/up pair) and RT row tiles,
-// RT = 8 or 6: one workgroup fits a compute unit, so the launch runs in rounds of n_cu workgroups and
+// RT = 5..8: one workgroup fits a compute unit, so the launch runs in rounds of n_cu workgroups and
 // the row-block height that needs the least rounds x height wins (1535 rows on 256 units: 6, where
 // QKV is 3.0 rounds instead of 2.25 and O / down exactly 1.0 instead of 0.75).
 template <int EPI, int FT>
@@ -671,9 +723,18 @@ static void launch_panel_epi(const GemmArgs &a, hipStream_t st) {
     }
     const int fb = ((a.plan.tasks + 8 * FT - 1) / (8 * FT) + 7) / 8 * 8;
     const int row_tiles = (a.rows + 15) / 16;
-    auto cost = [&](int rt) { return (long)((fb * ((row_tiles + rt - 1) / rt) + n_cu - 1) / n_cu) * rt; };
-    if (cost(6) < cost(8)) launch_panel_cfg<6, EPI, FT, 8>(a, st);
-    else launch_panel_cfg<8, EPI, FT, 8>(a, st);
+    const int ns = a.ksplit > 1 ? a.ksplit : 1;
+    auto cost = [&](int rt) { return (long)((fb * ((row_tiles + rt - 1) / rt) * ns + n_cu - 1) / n_cu) * rt; };
+    int best = 8;
+    for (int rt = 7; rt >= 5; --rt)
+        if (cost(rt) < cost(best)) best = rt;
+    switch (best) {
+        case 5: launch_panel_cfg<5, EPI, FT, 8>(a, st); break;
+        case 6: launch_panel_cfg<6, EPI, FT, 8>(a, st); break;
+        case 7: launch_panel_cfg<7, EPI, FT, 8>(a, st); break;
+        default: launch_panel_cfg<8, EPI, FT, 8>(a, st); break;
+    }
+    if (a.ksplit > 1) launch_splitk_finish<EPI>(a, st);
 }
 void launch_gemm_panel_bf16(const GemmArgs &a, hipStream_t st) {
     switch (a.epi) {
@@ -720,6 +781,14 @@ GemmPlan make_gemm_plan(int N, int K, int tiles_per_task) {
     // (waves x tiles per workgroup <= 48 keeps the wave-order reduction of three row tiles inside LDS)
     p.tk_ft = (tiles_per_task == 2) ? 1 : (p.tasks >= 640 ? 3 : 1);
     p.tk_waves = p.tk_ft > 1 ? 16 : 8;
+    // split-K form of the panel kernel: enough ranges that feature blocks x ranges is about 200
+    // workgroups per row block (2..8, a function of the matrix only, so a row's sums do not depend on
+    // how many rows share the step)
+    const int fb = (p.tasks + (tiles_per_task == 2 ? 8 : 16) - 1) / (tiles_per_task == 2 ? 8 : 16);
+    int ns = (192 + fb / 2) / fb;
+    ns = ns < 2 ? 2 : (ns > 8 ? 8 : ns);
+    const int chunks = (p.KSp + PANEL_KC - 1) / PANEL_KC;
+    p.n_split = ns < chunks ? ns : (chunks > 0 ? chunks : 1);
     return p;
 }
 

@@ -58,6 +58,7 @@ struct llma_ctx {
     float *h = nullptr, *qkv = nullptr;
     void *xhi = nullptr, *xlo = nullptr, *q = nullptr, *q_lo = nullptr, *att_hi = nullptr, *att_lo = nullptr, *act_hi = nullptr, *act_lo = nullptr;
     float *po = nullptr, *pm = nullptr, *pl = nullptr;
+    float *part = nullptr;             // split-K partial sums (contexts whose steps can exceed 48 rows)
     int nc_max = 0;
     // bf16 GEMM work division, per-tile sums of squares of the residual rows, rstd of prompt rows
     GemmPlan plan_qkv{}, plan_o{}, plan_gu{}, plan_down{}, plan_lm{};
@@ -242,6 +243,16 @@ static int create_impl(llma_ctx *c, const llma_weights *w) {
         // attention partials: [sequences][heads][chunks][rows], up to 48 rows per sequence (longer
         // prompt passes run the walking kernel, which has no partials)
         const size_t np = (size_t)g.max_batch * H * c->nc_max * 48;
+        // partial sums of the split-K GEMM of batched steps (more than 48 rows in a step)
+        const int step_rows = g.max_batch * (g.max_k + 1);
+        if (step_rows > 48) {
+            size_t tiles = 0;
+            for (const GemmPlan *pl : {&c->plan_qkv, &c->plan_o, &c->plan_gu, &c->plan_down, &c->plan_lm}) {
+                const size_t t = (size_t)pl->n_split * pl->tasks * (pl == &c->plan_gu ? 2 : 1);
+                tiles = t > tiles ? t : tiles;
+            }
+            ALLOC(c, c->part, tiles * ((step_rows + 15) / 16) * 1024);
+        }
         ALLOC(c, c->po, np * dh * 4);
         ALLOC(c, c->pm, np * 4);
         ALLOC(c, c->pl, np * 4);
@@ -381,10 +392,14 @@ static int forward_bf16(llma_ctx *c, int n_seqs, int m, int n_chunks, bool lm_he
     launch_embed_prep_bf16(c->embed, c->s.row_tok, c->n1[0], c->h, c->xhi, c->xlo, c->ssq, R, d, ksp_d, st);
     GemmArgs base{};
     base.rows = R; base.split = c->opt_split; base.eps = g.rms_eps;
-    // prompt passes (no LM head) and batched steps with more than 256 rows use the panel GEMM (weights
-    // streamed once for all rows, MFMA-bound, needs a few hundred rows to fill the chip); other steps
-    // the tile-K GEMM, in blocks of 48 rows
-    const bool panel = !lm_head || R > 256;
+    // prompt passes (no LM head) and batched steps of more than 48 rows use the panel GEMM (weights
+    // streamed once for all rows); the steps in its split-K form, because a few hundred rows alone make
+    // too few workgroups to fill the chip.  Steps of up to 48 rows use the tile-K GEMM.
+    const bool panel = !lm_head || R > 48;
+    auto panel_gemm = [&](GemmArgs &ga) {
+        if (lm_head && ga.plan.n_split > 1) { ga.ksplit = ga.plan.n_split; ga.part = c->part; }
+        launch_gemm_panel_bf16(ga, st);
+    };
     base.rstd_in = c->rstd;
     base.ssq_tiles = d / 16; base.H = H; base.dh = dh; base.max_seq = c->seq_cap; base.nx_KSp = ksp_d;
     AttnArgs aa{};
@@ -396,20 +411,20 @@ static int forward_bf16(llma_ctx *c, int n_seqs, int m, int n_chunks, bool lm_he
         ga.W = c->wqkv[l]; ga.plan = c->plan_qkv; ga.Xhi = c->xhi; ga.Xlo = c->xlo; ga.epi = EPI_QKV; ga.ssq_in = c->ssq;
         ga.row_pos = c->s.row_pos; ga.row_slot = c->s.row_slot; ga.row_cs = c->s.row_cs; ga.q_hi = c->q; ga.q_lo = c->q_lo;
         ga.k_hi = c->kc[l]; ga.k_lo = c->kc_lo[l]; ga.v_hi = c->vc[l]; ga.v_lo = c->vc_lo[l];
-        if (panel) { launch_rstd_rows(c->ssq, d / 16, g.rms_eps, c->rstd, R, st); launch_gemm_panel_bf16(ga, st); }
+        if (panel) { launch_rstd_rows(c->ssq, d / 16, g.rms_eps, c->rstd, R, st); panel_gemm(ga); }
         else launch_gemm_bf16(ga, st);
         aa.Khi = c->kc[l]; aa.Klo = c->kc_lo[l]; aa.Vhi = c->vc[l]; aa.Vlo = c->vc_lo[l];
         launch_attn_bf16(aa, st);
         ga = base;
         ga.W = c->wo[l]; ga.plan = c->plan_o; ga.Xhi = c->att_hi; ga.Xlo = c->att_lo; ga.epi = EPI_RESID; ga.out = c->h;
         ga.gain = c->n2[l]; ga.nx_hi = c->xhi; ga.nx_lo = c->xlo; ga.ssq_out = c->ssq;
-        panel ? launch_gemm_panel_bf16(ga, st) : launch_gemm_bf16(ga, st);
+        if (panel) panel_gemm(ga); else launch_gemm_bf16(ga, st);
         ga = base;
         ga.W = c->wgu[l]; ga.plan = c->plan_gu; ga.Xhi = c->xhi; ga.Xlo = c->xlo; ga.epi = EPI_SWIGLU; ga.ssq_in = c->ssq;
         ga.act_hi = c->act_hi; ga.act_lo = c->act_lo; ga.act_KSp = c->plan_down.KSp;
         if (panel) {
             launch_rstd_rows(c->ssq, d / 16, g.rms_eps, c->rstd, R, st);
-            launch_gemm_panel_bf16(ga, st);
+            panel_gemm(ga);
         } else if (c->opt_timing) {
             EventPair ep;
             HIP_TRY(c, hipEventCreate(&ep.a));
@@ -424,13 +439,13 @@ static int forward_bf16(llma_ctx *c, int n_seqs, int m, int n_chunks, bool lm_he
         ga = base;
         ga.W = c->wd[l]; ga.plan = c->plan_down; ga.Xhi = c->act_hi; ga.Xlo = c->act_lo; ga.epi = EPI_RESID; ga.out = c->h;
         ga.gain = (l + 1 < L) ? c->n1[l + 1] : c->final_norm; ga.nx_hi = c->xhi; ga.nx_lo = c->xlo; ga.ssq_out = c->ssq;
-        panel ? launch_gemm_panel_bf16(ga, st) : launch_gemm_bf16(ga, st);
+        if (panel) panel_gemm(ga); else launch_gemm_bf16(ga, st);
     }
     if (lm_head) {
         GemmArgs ga = base;
         ga.W = c->lm_head; ga.plan = c->plan_lm; ga.Xhi = c->xhi; ga.Xlo = c->xlo; ga.epi = EPI_LMHEAD; ga.ssq_in = c->ssq;
         ga.out = c->logits_dump; ga.pval = c->pval; ga.pidx = c->pidx; ga.n_part = c->n_part;
-        if (panel) { launch_rstd_rows(c->ssq, d / 16, g.rms_eps, c->rstd, R, st); launch_gemm_panel_bf16(ga, st); }
+        if (panel) { launch_rstd_rows(c->ssq, d / 16, g.rms_eps, c->rstd, R, st); panel_gemm(ga); }
         else launch_gemm_bf16(ga, st);
     }
     HIP_TRY(c, hipGetLastError());
