@@ -190,6 +190,41 @@ def test_batched_generate_small(llma):
     ctx.close()
 
 
+def test_batched_generate_wide_steps_small(llma):
+    """Eight sequences x (k + 1 = 7) rows = 56 rows per step: the steps run the split-K GEMM instead of
+    the decoding GEMM.  Same tokens as the single-sequence calls, except where the oracle shows a
+    near-tie at the first differing position (the two GEMMs add in different orders)."""
+    cfg = synth.SMALL
+    seed, max_new, n, k, B = 4321, 40, 1, 6, 8
+    w = synth.make_weights(cfg, seed)
+    om = OracleModel(cfg, w)
+    prompts = [synth.uniform_tokens(seed, 500 + i, 24 + 5 * i, cfg.vocab) for i in range(B)]
+    cap = 24 + 5 * B + max_new + 40
+    ctx = llma.Context(cfg, w, max_seq=cap, max_batch=B, max_k=8)
+    singles0 = [ctx.generate(p, None, None, 1, 0, max_new)[0] for p in prompts]
+    refs = [(synth.make_ref(y, 0.6, 8.0, 80, cfg.vocab, seed + i)[0], np.asarray([0, 80], dtype=np.int32)) for i, y in enumerate(singles0)]
+    singles = [ctx.generate(p, r[0], r[1], n, k, max_new) for p, r in zip(prompts, refs)]
+    batch = ctx.generate_batch(prompts, refs, n, k, max_new)
+    same = 0
+    for b in range(B):
+        gb, gs = batch[b][0], singles[b][0]
+        assert len(gb) == max_new
+        diff = next((i for i in range(max_new) if gb[i] != gs[i]), None)
+        if diff is None:
+            assert batch[b][1] == singles[b][1]
+            same += 1
+            continue
+        # legitimate only at a near-tie: the oracle's logits at that position, on the common prefix
+        ctxt = np.concatenate([prompts[b], gs[:diff]]).astype(np.int32)
+        cache = om.new_cache(len(ctxt) + 8)
+        lg = om.forward(ctxt, cache, 0)[-1]
+        assert top2_gap(lg) <= ATOL + RTOL * abs(float(lg.max())), (b, diff, top2_gap(lg))
+        print(f"  sequence {b}: near-tie at token {diff} (gap {top2_gap(lg):.2e})")
+    assert same >= B // 2
+    print(f"batched generate, 56-row steps: {same} of {B} sequences bit-identical to their single-sequence runs")
+    ctx.close()
+
+
 # --------------------------------------------------------------------------- 7B shape, full depth
 @pytest.mark.timeout(600)
 def test_7b_shape_verify_step_logits(llma):
