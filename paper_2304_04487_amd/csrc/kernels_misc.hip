@@ -117,18 +117,18 @@ void launch_rope_kv_f32(const float *qkv, const StepState &s, const float *cs_ta
 // o_a becomes the pending token.
 __global__ __launch_bounds__(256) void argmax_accept_kernel(const float *__restrict__ pval, const int *__restrict__ pidx,
                                                             int n_part, StepState s, int m, int max_k, const GenState *gen) {
-    __shared__ float wv[4];
-    __shared__ int wi[4];
     __shared__ int o[40];
     const int b = blockIdx.x;
     if (gen != nullptr) gen += b;                                // llma_generate: one GenState per sequence of the batch
     if (gen != nullptr && *gen->n_out >= gen->max_new) return;   // a finished sequence / a step enqueued past the end: leave all state alone
     const int keff = s.keff[b];
-    for (int j = 0; j <= keff; ++j) {
+    // one row per wave at a time: wave w reduces rows w, w + 4, ... over the per-tile partials
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int j = wave; j <= keff; j += 4) {
         const size_t r = (size_t)b * m + j;
         float bv = LLMA_NEG_INF;
         int bi = 0x7fffffff;
-        for (int t = threadIdx.x; t < n_part; t += 256) {
+        for (int t = lane; t < n_part; t += 64) {
             float v = pval[r * n_part + t];
             int id = pidx[r * n_part + t];
             if (v > bv || (v == bv && id < bi)) { bv = v; bi = id; }
@@ -139,16 +139,9 @@ __global__ __launch_bounds__(256) void argmax_accept_kernel(const float *__restr
             int oi = __shfl_xor(bi, off);
             if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
         }
-        if ((threadIdx.x & 63) == 0) { wv[threadIdx.x >> 6] = bv; wi[threadIdx.x >> 6] = bi; }
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            for (int w = 1; w < 4; ++w)
-                if (wv[w] > bv || (wv[w] == bv && wi[w] < bi)) { bv = wv[w]; bi = wi[w]; }
-            o[j] = bi;
-            s.otok[r] = bi;
-        }
-        __syncthreads();
+        if (lane == 0) { o[j] = bi; s.otok[r] = bi; }
     }
+    __syncthreads();
     if (threadIdx.x != 0) return;
     int a = 0;
     while (a < keff && o[a] == s.draft[b * max_k + a]) ++a;
