@@ -468,7 +468,7 @@ static void launch_gemm_nt(const GemmArgs &a, hipStream_t st) {
 
 // ---------------------------------------------------------------------------------------------
 // Panel GEMM for prompt processing (hundreds of rows): a workgroup computes a block of
-// 4*FT feature tiles x RT row tiles over the whole K axis -- no K split, no partial sums.  The
+// WV*FT feature tiles x RT row tiles over the whole K axis -- no K split, no partial sums.  The
 // block's activation rows are staged through LDS in chunks of KC k-steps (double-buffered,
 // 16-byte pieces gathered from the planes' row-major piece order into lane order) and shared by the
 // waves; every wave streams the weight blocks of its own FT feature tiles (TILES each) from
@@ -487,9 +487,10 @@ __device__ __forceinline__ void offset_rows(GemmArgs &a, const GemmPlan &p, int 
     if (a.q_hi) { a.q_hi = (bf16_t *)a.q_hi + (size_t)t0 * (a.H * a.dh / 32) * 512; a.q_lo = (bf16_t *)a.q_lo + (size_t)t0 * (a.H * a.dh / 32) * 512; }
 }
 
-#define PANEL_KC 2
+#define PANEL_KC 2          // k-steps per LDS chunk
+#define PANEL_WV 4          // waves per workgroup (two workgroups share a compute unit)
 template <int RT, int EPI, int FT, int WV>
-__global__ __launch_bounds__(WV * 64) void gemm_panel_bf16(GemmArgs a0) {
+__global__ __launch_bounds__(WV * 64, 2) void gemm_panel_bf16(GemmArgs a0) {
     constexpr int NTHR = WV * 64;
     constexpr int TILES = (EPI == EPI_SWIGLU) ? 2 : 1;
     constexpr int AT = FT * TILES;
@@ -708,10 +709,11 @@ static void launch_panel_cfg(const GemmArgs &a, hipStream_t st) {
 }
 
 // prompt-processing GEMM over any number of rows (needs a.rstd_in for the norm-scaled epilogues).
-// A workgroup owns 8 waves x FT feature tiles (FT = 2; SwiGLU: one gate/up pair) and RT row tiles,
-// RT = 5..8: one workgroup fits a compute unit, so the launch runs in rounds of n_cu workgroups and
-// the row-block height that needs the least rounds x height wins (1535 rows on 256 units: 6, where
-// QKV is 3.0 rounds instead of 2.25 and O / down exactly 1.0 instead of 0.75).
+// A workgroup owns 4 waves x FT feature tiles (FT = 2; SwiGLU: one gate/up pair) and RT row tiles,
+// RT = 5..8; two such workgroups fit a compute unit (their chunk barriers fall at different times,
+// which keeps the MFMA pipe busier than one workgroup of 8 waves did), so the launch runs in rounds
+// of 2 n_cu workgroups and the row-block height that needs the least rounds x height wins (1535 rows
+// on 256 units: 6, where QKV is 3.0 rounds instead of 2.25 and O / down exactly 1.0 instead of 0.75).
 template <int EPI, int FT>
 static void launch_panel_epi(const GemmArgs &a, hipStream_t st) {
     static int n_cu = 0;
@@ -721,18 +723,20 @@ static void launch_panel_epi(const GemmArgs &a, hipStream_t st) {
         if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n_cu = prop.multiProcessorCount;
         if (n_cu <= 0) n_cu = 256;
     }
-    const int fb = ((a.plan.tasks + 8 * FT - 1) / (8 * FT) + 7) / 8 * 8;
+    constexpr int WV = PANEL_WV;
+    const int slots = n_cu * (8 / WV);                   // workgroups resident at once
+    const int fb = ((a.plan.tasks + WV * FT - 1) / (WV * FT) + 7) / 8 * 8;
     const int row_tiles = (a.rows + 15) / 16;
     const int ns = a.ksplit > 1 ? a.ksplit : 1;
-    auto cost = [&](int rt) { return (long)((fb * ((row_tiles + rt - 1) / rt) * ns + n_cu - 1) / n_cu) * rt; };
+    auto cost = [&](int rt) { return (long)((fb * ((row_tiles + rt - 1) / rt) * ns + slots - 1) / slots) * rt; };
     int best = 8;
     for (int rt = 7; rt >= 5; --rt)
         if (cost(rt) < cost(best)) best = rt;
     switch (best) {
-        case 5: launch_panel_cfg<5, EPI, FT, 8>(a, st); break;
-        case 6: launch_panel_cfg<6, EPI, FT, 8>(a, st); break;
-        case 7: launch_panel_cfg<7, EPI, FT, 8>(a, st); break;
-        default: launch_panel_cfg<8, EPI, FT, 8>(a, st); break;
+        case 5: launch_panel_cfg<5, EPI, FT, WV>(a, st); break;
+        case 6: launch_panel_cfg<6, EPI, FT, WV>(a, st); break;
+        case 7: launch_panel_cfg<7, EPI, FT, WV>(a, st); break;
+        default: launch_panel_cfg<8, EPI, FT, WV>(a, st); break;
     }
     if (a.ksplit > 1) launch_splitk_finish<EPI>(a, st);
 }
