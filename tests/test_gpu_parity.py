@@ -276,6 +276,30 @@ def test_generate_degenerate_cases(llma):
     ctx.close()
 
 
+def test_ffn_gemm_timer_runs_and_checks_arguments(llma):
+    """The benchmark's timing entry point: plausible result on a small bf16 model, state untouched,
+    bad arguments rejected (and it refuses fp32 models)."""
+    cfg = MINI64
+    w = synth.make_weights(cfg, 3)
+    ctx = llma.Context(cfg, w, max_seq=64, max_batch=1, max_k=8)
+    ctx.prefill([1, 2, 3, 4])
+    st = ctx.get_state()
+    us = ctx.time_ffn_gemm(9, 16)
+    assert 0.5 < us < 1000.0 and ctx.get_state() == st
+    for rows, reps in ((0, 4), (10, 4), (49, 4), (4, 0)):          # rows beyond max_batch (max_k + 1) = 9, or none
+        with pytest.raises(llma.LlmaError) as e:
+            ctx.time_ffn_gemm(rows, reps)
+        assert e.value.code == llma.LLMA_E_RANGE
+    na, nxt, em = ctx.verify_step([5, 6])
+    assert ctx.get_state()[0] == st[0] + na + 1
+    ctx.close()
+    ctx = llma.Context(synth.TINY, synth.make_weights(synth.TINY, 3), max_seq=64, max_batch=1, max_k=4)
+    with pytest.raises(llma.LlmaError) as e:
+        ctx.time_ffn_gemm(2, 2)
+    assert e.value.code == llma.LLMA_E_INVAL
+    ctx.close()
+
+
 def test_argument_errors_leave_context_unchanged(llma):
     cfg = synth.TINY
     w = synth.make_weights(cfg, 1)
