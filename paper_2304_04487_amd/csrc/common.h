@@ -101,6 +101,7 @@ struct GemmArgs {          // bf16 path (fields marked f32 are used by the fp32 
     int ssq_tiles;         //   rstd[row] = rsqrt(sum / (16 ssq_tiles) + eps)
     float eps;
     const float *rstd_in;  // panel GEMM only: [rows] precomputed rstd (instead of ssq_in)
+    const int *rows_live;  // tile-K GEMM only, may be null: device int, rows 0 .. *rows_live carry tokens (the rest of `rows` is padding)
     int panel_rb;          // panel GEMM only: row blocks (set by the launcher)
     int ksplit;            // panel GEMM only: > 1 = the K axis is cut into this many ranges of k-chunks, partial sums via `part`
     float *part;           //   [ksplit][tiles][row tiles][64 lanes x 4] fp32 partial sums (register images)
@@ -133,6 +134,7 @@ struct AttnArgs {
     int n_seqs, m;          // rows per sequence
     int H, dh, max_seq;
     int n_chunks;           // launched chunks (upper bound over the batch)
+    const int *rows_live;   // may be null: device int, rows 0 .. *rows_live of the (single) sequence carry tokens
     int n_rblocks;          // row blocks per sequence (set by the launcher)
     float scale;
     float *po, *pm, *pl;    // partials

@@ -306,6 +306,13 @@ __global__ __launch_bounds__((TileKShape<NT, FT>::MAX_THREADS)) void gemm_tilek_
     constexpr int PL = SPLIT ? 2 : 1;
     extern __shared__ f32x4 red[];                 // [S][AT][NT][64], then rstd[16*NT] floats
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, S = (blockDim.x >> 6) * SL;
+    // llma_generate launches k + 1 rows in every step; how many of them carry a token (1 + the
+    // drafts the trigger found) is only known on the device.  The dead rows cost nothing here:
+    // their lanes re-read the first row's operands and the epilogue skips them.
+    if (a.rows_live != nullptr) {
+        const int live = *a.rows_live + 1;
+        a.rows = live < a.rows ? live : a.rows;
+    }
     const GemmPlan &p = a.plan;
     const int KSp = p.KSp;
     const int task0 = blockIdx.x * FT;
@@ -322,6 +329,7 @@ __global__ __launch_bounds__((TileKShape<NT, FT>::MAX_THREADS)) void gemm_tilek_
             wp[f * TILES + i] = (const u32x4 *)a.W + ((size_t)(task + i * p.tasks) * KSp) * 64 + lane;
         }
     const u32x4 *xh = (const u32x4 *)a.Xhi, *xl = (const u32x4 *)a.Xlo;
+    const int nt_live = (a.rows + 15) >> 4;        // row tiles with at least one live row (uniform)
     int xpc[NT];                                   // lanes of rows past the end re-read the tile's first row:
 #pragma unroll                                     // no extra cache line, no divergence; their results are dropped
     for (int t = 0; t < NT; ++t) xpc[t] = (t * 16 + (lane & 15) < a.rows) ? xtile_piece(lane) : (lane >> 4);
@@ -334,10 +342,11 @@ __global__ __launch_bounds__((TileKShape<NT, FT>::MAX_THREADS)) void gemm_tilek_
 #pragma unroll
             for (int i = 0; i < AT; ++i) av[i][u] = __builtin_nontemporal_load(wp[i] + (size_t)k * 64);
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                bv[0][t][u] = xh[((size_t)t * KSp + k) * 64 + xpc[t]];
-                if (SPLIT) bv[PL - 1][t][u] = xl[((size_t)t * KSp + k) * 64 + xpc[t]];
-            }
+            for (int t = 0; t < NT; ++t)
+                if (t == 0 || t < nt_live) {           // a row tile without a live row is skipped altogether
+                    bv[0][t][u] = xh[((size_t)t * KSp + k) * 64 + xpc[t]];
+                    if (SPLIT) bv[PL - 1][t][u] = xl[((size_t)t * KSp + k) * 64 + xpc[t]];
+                }
         }
     };
     f32x4 acc[AT][NT];
@@ -347,6 +356,7 @@ __global__ __launch_bounds__((TileKShape<NT, FT>::MAX_THREADS)) void gemm_tilek_
             if (ks + u < ks1) {
 #pragma unroll
                 for (int t = 0; t < NT; ++t)
+                    if (t == 0 || t < nt_live)
 #pragma unroll
                     for (int i = 0; i < AT; ++i) {
                         acc[i][t] = mfma16x16x32(av[i][u], bv[0][t][u], acc[i][t]);
@@ -826,7 +836,6 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
     const int slot = a.slot_const >= 0 ? a.slot_const : a.batch_slots[b];
     const int m = a.m;
     const int j0 = rb * RQ;                             // first row of this row block
-    const int m_blk = (m - j0 < RQ) ? m - j0 : RQ;      // rows of this block
     const int chunk0 = c * ATTN_CHUNK;
     const int d_model = a.H * DH;
     const int key0 = chunk0 + wave * 32;
@@ -866,6 +875,11 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
     }
     if (NTQ == 1) loads_stay_above();                   // (with more row tiles the registers are needed elsewhere)
     const int T = a.T[slot];
+    // generation steps: rows past the trigger's draft count are padding (see the GEMM); they are
+    // masked like rows past m and a row tile made of them only is skipped
+    const int m_live = (a.rows_live != nullptr && *a.rows_live + 1 < m) ? *a.rows_live + 1 : m;
+    if (j0 >= m_live) return;
+    const int m_blk = (m_live - j0 < RQ) ? m_live - j0 : RQ;   // live rows of this block
     const int kv_len = T + j0 + m_blk;                  // positions the block's last row can see
     if (chunk0 >= kv_len) return;                       // uniform for the workgroup
     const bool active = key0 < kv_len;                  // uniform for the wave
@@ -883,8 +897,9 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
     if (active) {
 #pragma unroll
         for (int q = 0; q < NTQ; ++q) {
+            if (q > 0 && j0 + q * 16 >= m_live) continue;        // uniform: no live row in this tile
             const int j = j0 + q * 16 + n;
-            const bool valid = j < m;
+            const bool valid = j < m_live;
             const int rpos = valid ? T + j : -1;
             const int r = b * m + (valid ? j : 0);
             u32x4 qh[KSTEPS], ql[KSTEPS];
@@ -990,6 +1005,7 @@ __global__ void attn_combine_bf16_kernel(AttnArgs a, int rq) {
     const int r = blockIdx.x, h = blockIdx.y;
     const int b = r / a.m, j = r % a.m;
     const int slot = a.slot_const >= 0 ? a.slot_const : a.batch_slots[b];
+    if (a.rows_live != nullptr && j > *a.rows_live) return;     // padding row of a generation step
     const int d4 = threadIdx.x;                        // features 4 d4 .. +3
     const size_t base = ((size_t)b * a.H + h) * a.n_chunks;
     // the first batch of partials is requested before the row's position is known: every launched

@@ -58,6 +58,7 @@ struct llma_ctx {
     float *h = nullptr, *qkv = nullptr;
     void *xhi = nullptr, *xlo = nullptr, *q = nullptr, *q_lo = nullptr, *att_hi = nullptr, *att_lo = nullptr, *act_hi = nullptr, *act_lo = nullptr;
     float *po = nullptr, *pm = nullptr, *pl = nullptr;
+    const int *rows_live = nullptr;    // set per step: device count of live rows - 1 (generation, one sequence) or null
     float *part = nullptr;             // split-K partial sums (contexts whose steps can exceed 48 rows)
     int nc_max = 0;
     // bf16 GEMM work division, per-tile sums of squares of the residual rows, rstd of prompt rows
@@ -392,6 +393,7 @@ static int forward_bf16(llma_ctx *c, int n_seqs, int m, int n_chunks, bool lm_he
     launch_embed_prep_bf16(c->embed, c->s.row_tok, c->n1[0], c->h, c->xhi, c->xlo, c->ssq, R, d, ksp_d, st);
     GemmArgs base{};
     base.rows = R; base.split = c->opt_split; base.eps = g.rms_eps;
+    base.rows_live = c->rows_live;                         // llma_generate, one sequence: the trigger's draft count (device)
     // prompt passes (no LM head) and batched steps of more than 48 rows use the panel GEMM (weights
     // streamed once for all rows); the steps in its split-K form, because a few hundred rows alone make
     // too few workgroups to fill the chip.  Steps of up to 48 rows use the tile-K GEMM.
@@ -404,6 +406,7 @@ static int forward_bf16(llma_ctx *c, int n_seqs, int m, int n_chunks, bool lm_he
     base.ssq_tiles = d / 16; base.H = H; base.dh = dh; base.max_seq = c->seq_cap; base.nx_KSp = ksp_d;
     AttnArgs aa{};
     aa.Qhi = c->q; aa.Qlo = c->q_lo; aa.T = c->s.T; aa.batch_slots = c->s.batch_slots; aa.slot_const = n_seqs == 1 ? slot : -1; aa.n_seqs = n_seqs; aa.m = m; aa.H = H; aa.dh = dh;
+    aa.rows_live = c->rows_live;
     aa.max_seq = c->seq_cap; aa.n_chunks = n_chunks; aa.scale = 1.0f / sqrtf((float)dh);
     aa.po = c->po; aa.pm = c->pm; aa.pl = c->pl; aa.out_hi = c->att_hi; aa.out_lo = c->att_lo; aa.out_KSp = ksp_d;
     for (int l = 0; l < L; ++l) {
@@ -463,6 +466,7 @@ static int forward(llma_ctx *c, int n_seqs, int m, int n_chunks, bool lm_head, i
 static int step_body(llma_ctx *c, int kind, int n_seqs, int m, int n_chunks, int slot) {
     hipStream_t st = c->run_st;
     const int mk = c->cfg.max_k;
+    c->rows_live = nullptr;
     if (kind == STEP_PREFILL) {
         launch_setup_prefill_rows(c->s, c->gen_prompt, c->gen_counters + 4 * c->cfg.max_batch, m, slot, c->cs_table, c->cfg.head_dim / 2, st);
         int rc = forward(c, 1, m, n_chunks, false, slot);
@@ -470,6 +474,7 @@ static int step_body(llma_ctx *c, int kind, int n_seqs, int m, int n_chunks, int
         launch_advance_T(c->s, slot, m, st);
         return LLMA_OK;
     }
+    c->rows_live = (kind == STEP_GEN && n_seqs == 1) ? c->s.keff : nullptr;
     if (kind == STEP_GEN) launch_trigger(c->gen_dev, c->s, n_seqs, mk, st);
     launch_setup_step_rows(c->s, n_seqs, m, mk, c->cs_table, c->cfg.head_dim / 2, st);
     int rc = forward(c, n_seqs, m, n_chunks, true, slot);
