@@ -128,10 +128,18 @@ __global__ __launch_bounds__(256) void argmax_accept_kernel(const float *__restr
         const size_t r = (size_t)b * m + j;
         float bv = LLMA_NEG_INF;
         int bi = 0x7fffffff;
-        for (int t = lane; t < n_part; t += 64) {
-            float v = pval[r * n_part + t];
-            int id = pidx[r * n_part + t];
-            if (v > bv || (v == bv && id < bi)) { bv = v; bi = id; }
+        for (int t0 = lane; t0 < n_part; t0 += 64 * 8) {      // 8 partials per lane in flight
+            float v[8];
+            int id[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int t = t0 + 64 * u;
+                v[u] = t < n_part ? pval[r * n_part + t] : LLMA_NEG_INF;
+                id[u] = t < n_part ? pidx[r * n_part + t] : 0x7fffffff;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (v[u] > bv || (v[u] == bv && id[u] < bi)) { bv = v[u]; bi = id[u]; }
         }
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) {
