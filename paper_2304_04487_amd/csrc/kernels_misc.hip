@@ -186,17 +186,31 @@ __device__ __forceinline__ unsigned long long scan_reference(const int *y, int i
                                                              const int *ref_doc, int ref_len, int n) {
     unsigned long long best = 0ull;
     if (i >= n) {
-        for (int p = threadIdx.x; p < ref_len; p += blockDim.x) {
-            const int pos = p - doc_offsets[ref_doc[p]];
-            if (pos < n) continue;
-            bool ok = true;
-            for (int t = 0; t < n; ++t)
-                if (ref[p - 1 - t] != y[i - 1 - t]) { ok = false; break; }
-            if (!ok) continue;
-            int score = n;
-            while (score < pos && score < i && ref[p - 1 - score] == y[i - 1 - score]) ++score;
-            unsigned long long key = ((unsigned long long)score << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned)p);
-            best = key > best ? key : best;
+        // first pass, eight positions per thread in flight: does the token before p equal the last
+        // token of y?  (necessary for a match; nearly all positions stop here)
+        const int last = y[i - 1];
+        for (int p0 = threadIdx.x; p0 < ref_len; p0 += blockDim.x * 8) {
+            int prev[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int p = p0 + u * blockDim.x;
+                prev[u] = (p >= 1 && p < ref_len) ? ref[p - 1] : -1;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int p = p0 + u * blockDim.x;
+                if (prev[u] != last || p >= ref_len) continue;      // (token ids are >= 0)
+                const int pos = p - doc_offsets[ref_doc[p]];
+                if (pos < n) continue;
+                bool ok = true;
+                for (int t = 1; t < n; ++t)
+                    if (ref[p - 1 - t] != y[i - 1 - t]) { ok = false; break; }
+                if (!ok) continue;
+                int score = n;
+                while (score < pos && score < i && ref[p - 1 - score] == y[i - 1 - score]) ++score;
+                unsigned long long key = ((unsigned long long)score << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned)p);
+                best = key > best ? key : best;
+            }
         }
     }
     // wave, then workgroup maximum
