@@ -276,6 +276,27 @@ def test_generate_degenerate_cases(llma):
     ctx.close()
 
 
+@pytest.mark.parametrize("cfg", [MINI64, MINI128], ids=lambda c: c.name)
+def test_generate_wide_drafts_bf16(llma, cfg):
+    """k up to the maximum (33 rows, three row tiles) on bf16 models: steps whose live row count
+    varies from 1 to 33 inside the same launch shape.  Same tokens as the library's plain greedy
+    decoding; step trace equal to the model-free prediction for that text (Algorithm 2)."""
+    w = synth.make_weights(cfg, 11)
+    prompt = synth.uniform_tokens(11, 1, 20, cfg.vocab)
+    N = 80
+    ctx = llma.Context(cfg, w, max_seq=20 + N + 40, max_batch=1, max_k=32)
+    y0, _ = ctx.generate(prompt, None, None, 1, 0, N)
+    ref, spans = synth.make_ref(y0, 0.7, 20.0, 160, cfg.vocab, seed=5)
+    offs = np.asarray([0, 70, 160], dtype=np.int32)
+    D = docs_from_flat(ref, offs)
+    for n, k in ((1, 32), (2, 17), (1, 16), (3, 31)):
+        g, t = ctx.generate(prompt, ref, offs, n, k, N)
+        assert np.array_equal(g, y0), (n, k)
+        assert t == infer_decoding_sequence(y0.tolist(), D, n, k), (n, k)
+        assert max(r for r, _, _, _ in t) > 9 or k < 9
+    ctx.close()
+
+
 def test_ffn_gemm_timer_runs_and_checks_arguments(llma):
     """The benchmark's timing entry point: plausible result on a small bf16 model, state untouched,
     bad arguments rejected (and it refuses fp32 models)."""
