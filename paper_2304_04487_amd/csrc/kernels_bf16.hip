@@ -498,7 +498,6 @@ __device__ __forceinline__ void offset_rows(GemmArgs &a, const GemmPlan &p, int 
 }
 
 #define PANEL_KC 2          // k-steps per LDS chunk
-#define PANEL_WV 4          // waves per workgroup (two workgroups share a compute unit)
 template <int RT, int EPI, int FT, int WV>
 __global__ __launch_bounds__(WV * 64, 2) void gemm_panel_bf16(GemmArgs a0) {
     constexpr int NTHR = WV * 64;
@@ -724,8 +723,8 @@ static void launch_panel_cfg(const GemmArgs &a, hipStream_t st) {
 // which keeps the MFMA pipe busier than one workgroup of 8 waves did), so the launch runs in rounds
 // of 2 n_cu workgroups and the row-block height that needs the least rounds x height wins (1535 rows
 // on 256 units: 6, where QKV is 3.0 rounds instead of 2.25 and O / down exactly 1.0 instead of 0.75).
-template <int EPI, int FT>
-static void launch_panel_epi(const GemmArgs &a, hipStream_t st) {
+template <int EPI, int FT, int WV>
+static void launch_panel_wv(const GemmArgs &a, hipStream_t st) {
     static int n_cu = 0;
     if (n_cu == 0) {
         int dev = 0;
@@ -733,7 +732,6 @@ static void launch_panel_epi(const GemmArgs &a, hipStream_t st) {
         if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n_cu = prop.multiProcessorCount;
         if (n_cu <= 0) n_cu = 256;
     }
-    constexpr int WV = PANEL_WV;
     const int slots = n_cu * (8 / WV);                   // workgroups resident at once
     const int fb = ((a.plan.tasks + WV * FT - 1) / (WV * FT) + 7) / 8 * 8;
     const int row_tiles = (a.rows + 15) / 16;
@@ -750,6 +748,14 @@ static void launch_panel_epi(const GemmArgs &a, hipStream_t st) {
     }
     if (a.ksplit > 1) launch_splitk_finish<EPI>(a, st);
 }
+// prompt passes: two 4-wave workgroups per compute unit (128-feature blocks); split-K steps: one
+// 8-wave workgroup (256-feature blocks), because with a few hundred rows and 2..8 K ranges the
+// activation rows every feature block stages are the larger part of the L2 traffic
+template <int EPI, int FT>
+static void launch_panel_epi(const GemmArgs &a, hipStream_t st) {
+    if (a.ksplit > 1) launch_panel_wv<EPI, FT, 8>(a, st);
+    else launch_panel_wv<EPI, FT, 4>(a, st);
+}
 void launch_gemm_panel_bf16(const GemmArgs &a, hipStream_t st) {
     switch (a.epi) {
         case EPI_RESID: launch_panel_epi<EPI_RESID, 2>(a, st); break;
@@ -759,8 +765,8 @@ void launch_gemm_panel_bf16(const GemmArgs &a, hipStream_t st) {
     }
 }
 
-// decoding-step GEMM: up to 48 rows (three row tiles) per launch; more rows (batched steps) are
-// processed in blocks of 48, re-streaming the weights per block
+// decoding-step GEMM: up to 48 rows (three row tiles) per launch (the callers send steps of more
+// rows to the panel kernel; should more arrive here, they are processed in blocks of 48)
 void launch_gemm_bf16(const GemmArgs &a0, hipStream_t st) {
     const GemmPlan &p = a0.plan;
     for (int r0 = 0; r0 < a0.rows; r0 += 48) {
@@ -822,7 +828,7 @@ __device__ __forceinline__ void loads_stay_above() { asm volatile("" ::: "memory
 // softmax statistics per query row, O^T = V^T . P^T (again hi/lo).  The four waves' (max, sum, O)
 // are merged in wave order, and the chunk's partial is written for the combine kernel.  Which
 // keys a row sees, and in which order they are reduced, is a function of absolute positions only.
-template <int DH, int NTQ, bool KVS>
+template <int DH, int NTQ, bool KVS, bool LIVE>
 __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
     constexpr int KSTEPS = DH / 32;   // MFMA k-steps of a q.k dot product
     constexpr int DT = DH / 16;       // 16-feature tiles of the head dimension
@@ -877,7 +883,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
     const int T = a.T[slot];
     // generation steps: rows past the trigger's draft count are padding (see the GEMM); they are
     // masked like rows past m and a row tile made of them only is skipped
-    const int m_live = (a.rows_live != nullptr && *a.rows_live + 1 < m) ? *a.rows_live + 1 : m;
+    const int m_live = (LIVE && *a.rows_live + 1 < m) ? *a.rows_live + 1 : m;     // LIVE: rows_live is set
     if (j0 >= m_live) return;
     const int m_blk = (m_live - j0 < RQ) ? m_live - j0 : RQ;   // live rows of this block
     const int kv_len = T + j0 + m_blk;                  // positions the block's last row can see
@@ -897,7 +903,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
     if (active) {
 #pragma unroll
         for (int q = 0; q < NTQ; ++q) {
-            if (q > 0 && j0 + q * 16 >= m_live) continue;        // uniform: no live row in this tile
+            if (LIVE && q > 0 && j0 + q * 16 >= m_live) continue;   // uniform: no live row in this tile
             const int j = j0 + q * 16 + n;
             const bool valid = j < m_live;
             const int rpos = valid ? T + j : -1;
@@ -1227,9 +1233,13 @@ static void launch_attn_dh(const AttnArgs &a0, hipStream_t st) {
     const int ntq = a.m > 32 ? 3 : (a.m + 15) / 16;
     a.n_rblocks = (a.m + ntq * 16 - 1) / (ntq * 16);
     dim3 grid(a.n_chunks, a.H, a.n_seqs * a.n_rblocks);
-    if (ntq == 1) hipLaunchKernelGGL((attn_bf16_kernel<DH, 1, KVS>), grid, dim3(256), 0, st, a);
-    else if (ntq == 2) hipLaunchKernelGGL((attn_bf16_kernel<DH, 2, KVS>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((attn_bf16_kernel<DH, 3, KVS>), grid, dim3(256), 0, st, a);
+    if (a.rows_live != nullptr) {                      // generation step of one sequence: padding rows known on the device
+        if (ntq == 1) hipLaunchKernelGGL((attn_bf16_kernel<DH, 1, KVS, true>), grid, dim3(256), 0, st, a);
+        else if (ntq == 2) hipLaunchKernelGGL((attn_bf16_kernel<DH, 2, KVS, true>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((attn_bf16_kernel<DH, 3, KVS, true>), grid, dim3(256), 0, st, a);
+    } else if (ntq == 1) hipLaunchKernelGGL((attn_bf16_kernel<DH, 1, KVS, false>), grid, dim3(256), 0, st, a);
+    else if (ntq == 2) hipLaunchKernelGGL((attn_bf16_kernel<DH, 2, KVS, false>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((attn_bf16_kernel<DH, 3, KVS, false>), grid, dim3(256), 0, st, a);
     hipLaunchKernelGGL((attn_combine_bf16_kernel<DH>), dim3(a.n_seqs * a.m, a.H), dim3(DH / 4), 0, st, a, a.n_rblocks * ntq * 16);
 }
 
