@@ -507,7 +507,7 @@ __global__ __launch_bounds__(WV * 64, 2) void gemm_panel_bf16(GemmArgs a0) {
     constexpr int CH = RT * KC * 64;               // 16-byte pieces per plane and chunk
     constexpr int PER = (2 * CH + NTHR - 1) / NTHR; // pieces per thread and chunk (both planes)
     extern __shared__ u32x4 xs[];                  // [2 buffers][2 planes][RT][KC][64], then rstd[16*RT]
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const GemmPlan &p = a0.plan;
     const int KSp = p.KSp;
     // Workgroup order: the row blocks of one feature block get ids that differ by multiples of 8, i.e.
@@ -523,48 +523,56 @@ __global__ __launch_bounds__(WV * 64, 2) void gemm_panel_bf16(GemmArgs a0) {
     offset_rows(a, p, r0);
     const int task0 = (fb * WV + wave) * FT;        // may lie past the last tile (padding feature blocks): clamped loads, no epilogue
 
-    const u32x4 *wp[AT];
+    const char *wb[AT];                            // first weight block of each tile (wave-uniform)
 #pragma unroll
     for (int f = 0; f < FT; ++f)
 #pragma unroll
         for (int i = 0; i < TILES; ++i) {
             int task = task0 + f;
             task = task < p.tasks ? task : p.tasks - 1;
-            wp[f * TILES + i] = (const u32x4 *)a.W + ((size_t)(task + i * p.tasks) * KSp) * 64 + lane;
+            wb[f * TILES + i] = (const char *)a.W + ((size_t)(task + i * p.tasks) * KSp) * 1024;
         }
-    const u32x4 *xh = (const u32x4 *)a.Xhi, *xl = (const u32x4 *)a.Xlo;
+    const char *xh = (const char *)a.Xhi, *xl = (const char *)a.Xlo;
     const int n_rt_total = (a0.rows + 15) / 16;    // row tiles that exist in the planes
 
-    // activation chunk kc -> registers (both planes); pieces of row tiles past the end read tile 0
+    // Operand fetches.  Every address below is a wave-uniform base (scalar registers, scalar
+    // arithmetic) plus one per-lane byte offset that never changes (the lane's 16 bytes of a 1 KiB
+    // block), so the chunk loop spends no vector instructions on addressing; every load is
+    // unconditional (indices are clamped instead): a load under a branch makes the compiler's count
+    // of loads in flight inexact, and it then waits for all of them.
+    // Activation chunk kc -> registers: wave w fetches the 1 KiB blocks q = j WV + w of the chunk's
+    // [2 planes][RT][KC] blocks; blocks of row tiles past the end read tile 0.
+    const unsigned x_lane = (unsigned)xtile_piece(lane) * 16u;     // LDS holds the block in lane order
+    const unsigned w_lane = (unsigned)lane * 16u;
     auto fetch_x = [&](int kc, u32x4 (&v)[PER]) {
 #pragma unroll
         for (int j = 0; j < PER; ++j) {
-            const int i = j * NTHR + threadIdx.x;
-            if (i < 2 * CH) {
-                const int pl = i / CH, rem = i % CH;
-                const int t = rem / (KC * 64), kk = (rem / 64) % KC, ln = rem % 64;
-                int k = kc * KC + kk;
-                k = k < KSp ? k : KSp - 1;
-                const int tt = (rt0 + t < n_rt_total) ? rt0 + t : 0;
-                const size_t src = ((size_t)tt * KSp + k) * 64 + xtile_piece(ln);   // LDS holds the block in lane order
-                v[j] = pl ? xl[src] : xh[src];
-            }
+            int q = j * WV + wave;
+            q = q < 2 * RT * KC ? q : 2 * RT * KC - 1;
+            const int pl = q / (RT * KC), t = (q % (RT * KC)) / KC, kk = q % KC;
+            int k = kc * KC + kk;
+            k = k < KSp ? k : KSp - 1;
+            const int tt = (rt0 + t < n_rt_total) ? rt0 + t : 0;
+            const char *blk = (const char *)(pl ? xl : xh) + ((size_t)tt * KSp + k) * 1024;
+            v[j] = *(const u32x4 *)(blk + x_lane);
         }
     };
     auto stash_x = [&](int buf, u32x4 (&v)[PER]) {
 #pragma unroll
         for (int j = 0; j < PER; ++j) {
-            const int i = j * NTHR + threadIdx.x;
-            if (i < 2 * CH) xs[buf * 2 * CH + i] = v[j];
+            const int q = j * WV + wave;
+            if (q < 2 * RT * KC) xs[(buf * 2 * RT * KC + q) * 64 + lane] = v[j];
         }
     };
+    // weights of chunk kc; a k-step past the end of K (ragged last chunk) gets zeros and adds nothing
     auto fetch_w = [&](int kc, u32x4 (&av)[AT][KC]) {
 #pragma unroll
         for (int u = 0; u < KC; ++u) {
-            int k = kc * KC + u;
-            k = k < KSp ? k : KSp - 1;
+            const int k0 = kc * KC + u;
+            const int k = k0 < KSp ? k0 : KSp - 1;
+            const unsigned keep = k0 < KSp ? 0xffffffffu : 0u;      // (a mask, not a select: the load stays unconditional)
 #pragma unroll
-            for (int i = 0; i < AT; ++i) av[i][u] = wp[i][(size_t)k * 64];
+            for (int i = 0; i < AT; ++i) av[i][u] = *(const u32x4 *)(wb[i] + (size_t)k * 1024 + w_lane) & keep;
         }
     };
 
@@ -587,30 +595,35 @@ __global__ __launch_bounds__(WV * 64, 2) void gemm_panel_bf16(GemmArgs a0) {
         for (int r = threadIdx.x; r < 16 * RT; r += NTHR) rstd_s[r] = (r < a.rows) ? a.rstd_in[r0 + r] : 0.f;
     stash_x(0, xv);
     __syncthreads();
-    for (int kc = kc_lo; kc < NC; ++kc) {
-        const int buf = (kc - kc_lo) & 1;
-        if (kc + 1 < NC) fetch_x(kc + 1, xv);
-        auto step = [&](u32x4 (&av)[AT][KC], u32x4 (&avn)[AT][KC]) {
-            if (kc + 1 < NC) fetch_w(kc + 1, avn);
+    // one chunk: request the next chunk's operands, run this chunk's MFMAs out of LDS buffer `buf`
+    // and weight registers `av`, park the next activation chunk in the other LDS buffer.  The loop
+    // below calls it twice per round with the buffers swapped, so that every register array has one
+    // fixed role per call site (one body taking either buffer made the compiler copy accumulators
+    // and weight registers between the two roles every chunk, behind a wait for all loads in flight).
+    auto chunk = [&](int kc, int buf, u32x4 (&av)[AT][KC], u32x4 (&avn)[AT][KC]) {
+        const int kn = kc + 1 < NC ? kc + 1 : kc;      // the last chunk requests itself again (unused)
+        fetch_x(kn, xv);
+        fetch_w(kn, avn);
 #pragma unroll
-            for (int u = 0; u < KC; ++u) {
-                if (kc * KC + u < KSp) {
+        for (int u = 0; u < KC; ++u) {
 #pragma unroll
-                    for (int t = 0; t < RT; ++t) {
-                        const u32x4 bh = xs[buf * 2 * CH + (t * KC + u) * 64 + lane];
-                        const u32x4 bl = xs[buf * 2 * CH + CH + (t * KC + u) * 64 + lane];
+            for (int t = 0; t < RT; ++t) {
+                const u32x4 bh = xs[buf * 2 * CH + (t * KC + u) * 64 + lane];
+                const u32x4 bl = xs[buf * 2 * CH + CH + (t * KC + u) * 64 + lane];
 #pragma unroll
-                        for (int i = 0; i < AT; ++i) {
-                            acc[i][t] = mfma16x16x32(av[i][u], bh, acc[i][t]);
-                            acc[i][t] = mfma16x16x32(av[i][u], bl, acc[i][t]);
-                        }
-                    }
+                for (int i = 0; i < AT; ++i) {
+                    acc[i][t] = mfma16x16x32(av[i][u], bh, acc[i][t]);
+                    acc[i][t] = mfma16x16x32(av[i][u], bl, acc[i][t]);
                 }
             }
-        };
-        if (buf == 0) step(avA, avB); else step(avB, avA);
-        if (kc + 1 < NC) stash_x(buf ^ 1, xv);     // the other buffer was last read before the previous barrier
+        }
+        stash_x(buf ^ 1, xv);                          // the other buffer was last read before the previous barrier
         __syncthreads();
+    };
+    for (int kc = kc_lo; kc < NC; kc += 2) {
+        chunk(kc, 0, avA, avB);
+        if (kc + 1 >= NC) break;
+        chunk(kc + 1, 1, avB, avA);
     }
 
     if (n_split > 1) {
