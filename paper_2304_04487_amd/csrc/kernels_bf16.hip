@@ -588,22 +588,24 @@ __global__ __launch_bounds__(WV * 64, 2) void gemm_panel_bf16(GemmArgs a0) {
     const int n_split = a0.ksplit > 1 ? a0.ksplit : 1;
     const int NC_all = (KSp + KC - 1) / KC;
     const int kc_lo = (int)((long)NC_all * blockIdx.y / n_split), NC = (int)((long)NC_all * (blockIdx.y + 1) / n_split);
-    u32x4 xv[PER], avA[AT][KC], avB[AT][KC];
-    fetch_x(kc_lo, xv);
+    u32x4 xvA[PER], xvB[PER], avA[AT][KC], avB[AT][KC];
+    fetch_x(kc_lo, xvA);
     fetch_w(kc_lo, avA);
+    fetch_x(kc_lo + 1 < NC ? kc_lo + 1 : kc_lo, xvB);
     if (EPI != EPI_RESID)
         for (int r = threadIdx.x; r < 16 * RT; r += NTHR) rstd_s[r] = (r < a.rows) ? a.rstd_in[r0 + r] : 0.f;
-    stash_x(0, xv);
+    stash_x(0, xvA);
     __syncthreads();
-    // one chunk: request the next chunk's operands, run this chunk's MFMAs out of LDS buffer `buf`
-    // and weight registers `av`, park the next activation chunk in the other LDS buffer.  The loop
-    // below calls it twice per round with the buffers swapped, so that every register array has one
-    // fixed role per call site (one body taking either buffer made the compiler copy accumulators
-    // and weight registers between the two roles every chunk, behind a wait for all loads in flight).
-    auto chunk = [&](int kc, int buf, u32x4 (&av)[AT][KC], u32x4 (&avn)[AT][KC]) {
-        const int kn = kc + 1 < NC ? kc + 1 : kc;      // the last chunk requests itself again (unused)
-        fetch_x(kn, xv);
-        fetch_w(kn, avn);
+    // One chunk: request operands (the weights of the next chunk, the activations of the chunk after
+    // it: they still have to pass through LDS), run this chunk's MFMAs out of LDS buffer `buf` and
+    // weight registers `av`, park the next chunk's activations (requested a chunk ago, `x_park`) in
+    // the other LDS buffer.  The loop below calls it twice per round with the buffers swapped, so
+    // that every register array has one fixed role per call site (one body taking either buffer made
+    // the compiler copy accumulators and weight registers between the two roles every chunk, behind
+    // a wait for all loads in flight).
+    auto chunk = [&](int kc, int buf, u32x4 (&av)[AT][KC], u32x4 (&avn)[AT][KC], u32x4 (&x_park)[PER], u32x4 (&x_req)[PER]) {
+        fetch_x(kc + 2 < NC ? kc + 2 : kc, x_req);     // (x_req held this chunk's activations, in LDS since the last barrier;
+        fetch_w(kc + 1 < NC ? kc + 1 : kc, avn);       //  the last chunks request themselves again, unused)
 #pragma unroll
         for (int u = 0; u < KC; ++u) {
 #pragma unroll
@@ -617,13 +619,13 @@ __global__ __launch_bounds__(WV * 64, 2) void gemm_panel_bf16(GemmArgs a0) {
                 }
             }
         }
-        stash_x(buf ^ 1, xv);                          // the other buffer was last read before the previous barrier
+        stash_x(buf ^ 1, x_park);                      // the other buffer was last read before the previous barrier
         __syncthreads();
     };
     for (int kc = kc_lo; kc < NC; kc += 2) {
-        chunk(kc, 0, avA, avB);
+        chunk(kc, 0, avA, avB, xvB, xvA);
         if (kc + 1 >= NC) break;
-        chunk(kc + 1, 1, avB, avA);
+        chunk(kc + 1, 1, avB, avA, xvA, xvB);
     }
 
     if (n_split > 1) {
