@@ -861,6 +861,11 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
     const int d_model = a.H * DH;
     const int key0 = chunk0 + wave * 32;
     const size_t head_base = ((size_t)slot * a.H + h) * (size_t)a.max_seq * DH;
+    // The sequence length and the live-row count are requested first and used last: both requests
+    // are in flight together with the K/V blocks instead of one after the other behind them.
+    const int T = a.T[slot];
+    const int live_rows = LIVE ? *a.rows_live + 1 : m;
+    loads_stay_above();
     // K and V blocks of the wave's 32 positions: issued before the sequence length is known (any
     // position below max_seq lies inside the cache allocation; unused blocks are simply dropped)
     u32x4 ka[2][KSTEPS], kb[2][KSTEPS], va[DT], vb[DT];
@@ -895,10 +900,9 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
         }
     }
     if (NTQ == 1) loads_stay_above();                   // (with more row tiles the registers are needed elsewhere)
-    const int T = a.T[slot];
     // generation steps: rows past the trigger's draft count are padding (see the GEMM); they are
     // masked like rows past m and a row tile made of them only is skipped
-    const int m_live = (LIVE && *a.rows_live + 1 < m) ? *a.rows_live + 1 : m;     // LIVE: rows_live is set
+    const int m_live = live_rows < m ? live_rows : m;     // LIVE: rows_live is set
     if (j0 >= m_live) return;
     const int m_blk = (m_live - j0 < RQ) ? m_live - j0 : RQ;   // live rows of this block
     const int kv_len = T + j0 + m_blk;                  // positions the block's last row can see
@@ -1026,7 +1030,11 @@ __global__ void attn_combine_bf16_kernel(AttnArgs a, int rq) {
     const int r = blockIdx.x, h = blockIdx.y;
     const int b = r / a.m, j = r % a.m;
     const int slot = a.slot_const >= 0 ? a.slot_const : a.batch_slots[b];
-    if (a.rows_live != nullptr && j > *a.rows_live) return;     // padding row of a generation step
+    // live-row count and sequence length: requested before the partials, used after them (one
+    // round trip to memory for all three instead of three in a row)
+    const int live_last = a.rows_live != nullptr ? *a.rows_live : a.m;
+    const int T = a.T[slot];
+    loads_stay_above();
     const int d4 = threadIdx.x;                        // features 4 d4 .. +3
     const size_t base = ((size_t)b * a.H + h) * a.n_chunks;
     // the first batch of partials is requested before the row's position is known: every launched
@@ -1044,7 +1052,8 @@ __global__ void attn_combine_bf16_kernel(AttnArgs a, int rq) {
     };
     fetch(0);
     loads_stay_above();
-    const int pos = a.T[slot] + j;
+    if (j > live_last) return;                         // padding row of a generation step (its partials are stale: dropped)
+    const int pos = T + j;
     const int nc = pos / ATTN_CHUNK + 1;
     // running (max, sum, O) over the chunks in chunk order
     float M = LLMA_NEG_INF, L = 0.f;
