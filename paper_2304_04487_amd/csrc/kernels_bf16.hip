@@ -309,13 +309,19 @@ __global__ __launch_bounds__((TileKShape<NT, FT>::MAX_THREADS)) void gemm_tilek_
     // llma_generate launches k + 1 rows in every step; how many of them carry a token (1 + the
     // drafts the trigger found) is only known on the device.  The dead rows cost nothing here:
     // their lanes re-read the first row's operands and the epilogue skips them.
-    if (a.rows_live != nullptr) {
-        const int live = *a.rows_live + 1;
-        a.rows = live < a.rows ? live : a.rows;
-    }
+    auto clamp_rows = [&]() {
+        if (a.rows_live != nullptr) {
+            const int live = *a.rows_live + 1;
+            a.rows = live < a.rows ? live : a.rows;
+        }
+    };
+    if (NT > 1) clamp_rows();
     const GemmPlan &p = a.plan;
     const int KSp = p.KSp;
     const int task0 = blockIdx.x * FT;
+    // slice boundaries floor(KSp * slice / S); S is 8 or 16 (a shift; a 64-bit division here costs
+    // a few hundred instructions before the kernel's first load)
+    const int s_sh = 31 - __builtin_clz(S);
     int ks1 = 0;                                   // end of the K slice being streamed
     float *rstd_s = (float *)(red + (size_t)S * AT * NT * 64);
 
@@ -328,17 +334,33 @@ __global__ __launch_bounds__((TileKShape<NT, FT>::MAX_THREADS)) void gemm_tilek_
             task = task < p.tasks ? task : p.tasks - 1;          // ragged last workgroup: recompute the last tile
             wp[f * TILES + i] = (const u32x4 *)a.W + ((size_t)(task + i * p.tasks) * KSp) * 64 + lane;
         }
+    // One row tile (the usual decoding step): the wave's first weight blocks are requested before
+    // the live-row count is read, which is a round trip to memory of its own.
+    u32x4 avA[AT][UB];
+    if (NT == 1) {
+        const int k_lo = (KSp * wave * SL) >> s_sh, k_hi = (KSp * (wave * SL + 1)) >> s_sh;
+        if (k_lo < k_hi) {
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                const int k = k_lo + u < k_hi ? k_lo + u : k_hi - 1;
+#pragma unroll
+                for (int i = 0; i < AT; ++i) avA[i][u] = __builtin_nontemporal_load(wp[i] + (size_t)k * 64);
+            }
+        }
+        clamp_rows();
+    }
     const u32x4 *xh = (const u32x4 *)a.Xhi, *xl = (const u32x4 *)a.Xlo;
     const int nt_live = (a.rows + 15) >> 4;        // row tiles with at least one live row (uniform)
     int xpc[NT];                                   // lanes of rows past the end re-read the tile's first row:
 #pragma unroll                                     // no extra cache line, no divergence; their results are dropped
     for (int t = 0; t < NT; ++t) xpc[t] = (t * 16 + (lane & 15) < a.rows) ? xtile_piece(lane) : (lane >> 4);
 
-    auto issue = [&](int ks, u32x4 (&av)[AT][UB], u32x4 (&bv)[PL][NT][UB]) {
+    auto issue = [&](int ks, u32x4 (&av)[AT][UB], u32x4 (&bv)[PL][NT][UB], bool weights = true) {
 #pragma unroll
         for (int u = 0; u < UB; ++u) {
             int k = ks + u;
             k = k < ks1 ? k : ks1 - 1;
+            if (weights)
 #pragma unroll
             for (int i = 0; i < AT; ++i) av[i][u] = __builtin_nontemporal_load(wp[i] + (size_t)k * 64);
 #pragma unroll
@@ -365,11 +387,11 @@ __global__ __launch_bounds__((TileKShape<NT, FT>::MAX_THREADS)) void gemm_tilek_
             }
     };
 
-    u32x4 avA[AT][UB], bvA[PL][NT][UB], avB[AT][UB], bvB[PL][NT][UB];
+    u32x4 bvA[PL][NT][UB], avB[AT][UB], bvB[PL][NT][UB];
     int slice = wave * SL;
-    int ks = (int)(((long)KSp * slice) / S);
-    ks1 = (int)(((long)KSp * (slice + 1)) / S);
-    if (ks < ks1) issue(ks, avA, bvA);
+    int ks = (KSp * slice) >> s_sh;
+    ks1 = (KSp * (slice + 1)) >> s_sh;
+    if (ks < ks1) issue(ks, avA, bvA, NT > 1);      // (one row tile: the weights are already on their way)
     // epilogue inputs and rstd while the first batch is in flight
     EpiIn<NT> in;
     const int my_task = task0 + wave;                           // waves 0..FT-1 finish one tile each
@@ -404,8 +426,8 @@ __global__ __launch_bounds__((TileKShape<NT, FT>::MAX_THREADS)) void gemm_tilek_
     for (int sl = 0; sl < SL; ++sl) {
         if (sl > 0) {
             slice = wave * SL + sl;
-            ks = (int)(((long)KSp * slice) / S);
-            ks1 = (int)(((long)KSp * (slice + 1)) / S);
+            ks = (KSp * slice) >> s_sh;
+            ks1 = (KSp * (slice + 1)) >> s_sh;
             if (ks < ks1) issue(ks, avA, bvA);
         }
 #pragma unroll
