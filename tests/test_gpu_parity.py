@@ -132,6 +132,83 @@ def test_verify_step_logits_and_state(llma, cfg):
     ctx.close()
 
 
+MINIODD = synth.ModelCfg("miniodd", 2, 192, 3, 64, 416, 1024, "bf16")
+
+
+def test_prompt_pass_and_steps_with_odd_k_step_counts(llma):
+    """d_ffn = 416 gives the down projection 13 MFMA k-steps (d_model = 192: 6): the prompt-pass GEMM's
+    last two-step chunk is half empty, the decoding GEMM's 8 K slices have 1 or 2 steps.  A 150-token prompt
+    (two row blocks, ragged) and steps of 1, 9 and 33 rows are compared with the oracle."""
+    cfg = MINIODD
+    w = synth.make_weights(cfg, 78, gain_jitter=0.3)
+    om = OracleModel(cfg, w)
+    prompt = synth.uniform_tokens(2, 6, 150, cfg.vocab)
+    ctx = llma.Context(cfg, w, max_seq=256, max_batch=1, max_k=32)
+    ctx.enable_logits_dump(33)
+    ctx.prefill(prompt)
+    cache = om.new_cache(256)
+    om.forward(prompt[:-1], cache, 0)
+    T, pending = len(prompt) - 1, int(prompt[-1])
+    assert ctx.get_state() == (T, pending)
+    atol, rtol = tol(cfg)
+    for step, k in enumerate([0, 8, 32]):
+        draft = [int(t) for t in synth.uniform_tokens(3, 40 + step, k, cfg.vocab)] if k else []
+        want_logits = om.forward([pending] + draft, cache, T)
+        o = argmax_tokens(want_logits)
+        a = 0
+        while a < k and o[a] == draft[a]:
+            a += 1
+        na, nxt, emitted = ctx.verify_step(draft)
+        got_logits = ctx.logits(k + 1)
+        assert_logits_close(got_logits, want_logits, cfg, f"odd k-steps, step {step} k={k}")
+        go = np.argmax(got_logits, axis=-1)
+        tie = any(go[j] != o[j] for j in range(k + 1))
+        for j in range(k + 1):
+            if go[j] != o[j]:
+                assert top2_gap(want_logits[j]) <= atol + rtol * abs(want_logits[j].max()), (step, j)
+        if not tie:
+            assert (na, nxt) == (a, int(o[a]))
+        else:
+            print("near-tie in step", step)
+            break
+        T += na + 1
+        pending = nxt
+        assert ctx.get_state() == (T, pending)
+    ctx.close()
+
+
+def test_batched_steps_with_odd_k_step_counts(llma):
+    """Eight sequences x 7 rows = 56 rows per step on the same odd shape: the split-K GEMM's K ranges
+    are single chunks, the last one half empty.  Tokens as in the single-sequence calls, except at
+    near-ties of the oracle's logits (the two GEMMs add in different orders)."""
+    cfg = MINIODD
+    seed, max_new, n, k, B = 99, 24, 1, 6, 8
+    w = synth.make_weights(cfg, seed, gain_jitter=0.3)
+    om = OracleModel(cfg, w)
+    atol, rtol = tol(cfg)
+    prompts = [synth.uniform_tokens(seed, 300 + i, 20 + 3 * i, cfg.vocab) for i in range(B)]
+    ctx = llma.Context(cfg, w, max_seq=128, max_batch=B, max_k=8)
+    plain = [ctx.generate(p, None, None, 1, 0, max_new)[0] for p in prompts]
+    refs = [(synth.make_ref(y, 0.6, 8.0, 48, cfg.vocab, seed + i)[0], np.asarray([0, 48], dtype=np.int32)) for i, y in enumerate(plain)]
+    singles = [ctx.generate(p, r[0], r[1], n, k, max_new) for p, r in zip(prompts, refs)]
+    batch = ctx.generate_batch(prompts, refs, n, k, max_new)
+    same = 0
+    for b in range(B):
+        gb, gs = batch[b][0], singles[b][0]
+        assert len(gb) == max_new
+        diff = next((i for i in range(max_new) if gb[i] != gs[i]), None)
+        if diff is None:
+            same += 1
+            continue
+        ctxt = np.concatenate([prompts[b], gs[:diff]]).astype(np.int32)
+        cache = om.new_cache(len(ctxt) + 8)
+        lg = om.forward(ctxt, cache, 0)[-1]
+        assert top2_gap(lg) <= atol + rtol * abs(float(lg.max())), (b, diff, top2_gap(lg))
+        print(f"  sequence {b}: near-tie at token {diff}")
+    assert same >= B // 2
+    ctx.close()
+
+
 @pytest.mark.parametrize("cfg", [MINIF32, MINI64], ids=lambda c: c.name)
 def test_repeated_same_shape_steps_replay_graphs_correctly(llma, cfg):
     """The step's launches are captured into a HIP graph the second time a shape is seen and
