@@ -279,6 +279,14 @@ def main():
     if not args.no_cpu_baseline:
         t0 = time.time()
         out["cpu_baseline"] = cpu_baseline(wl, wl.prompt_len)
+        # the paper's model-free prediction of the step sequence from the known output (its
+        # target-guided simulation), beside the realised one: also oracle code, so it lives here
+        from oracle.decode import infer_decoding_sequence, docs_from_flat
+        pred = infer_decoding_sequence([int(t) for t in y0], docs_from_flat(ref, offs), wl.n, k)
+        out["cpu_baseline"]["predicted_steps"] = len(pred)
+        out["cpu_baseline"]["predicted_tokens_per_step"] = round(wl.max_new / len(pred), 3)
+        out["cpu_baseline"]["predicted_trace_matches_gpu"] = bool(
+            len(pred) == len(trace) and all(int(a[0]) == int(b[0]) and int(a[1]) == int(b[1]) for a, b in zip(pred, trace)))
         log(f"[bench] cpu baseline took {time.time() - t0:.1f}s")
     print(json.dumps(out), flush=True)
 
