@@ -250,6 +250,18 @@ def main():
         "k0_decode_only_tokens_per_s": round(wl.max_new / (t_k0 - t_prefill), 2),
         "reference": "built from the library's own k=0 output: spans of it at 50% coverage, mean length 12, the rest uniform ids",
     }
+    # ---- mean step time by live row count: the same k with an empty reference gives steps of one
+    # live row (k + 1 rows launched, the rest masked on the device); the trigger steps' time follows
+    # from the two totals
+    n_trig = extras["triggers"]
+    if n_trig > 0 and steps > n_trig:
+        t_none, y_none, tr_none = timed_generate(None, None, wl.n, k, 2)
+        assert np.array_equal(y_none, y0) and len(tr_none) == wl.max_new
+        t_one = (t_none - t_prefill) / len(tr_none)
+        t_full = (t_decode - (steps - n_trig) * t_one) / n_trig
+        extras["step_ms_by_live_rows"] = {"1": round(t_one * 1e3, 4), str(k + 1): round(t_full * 1e3, 4),
+                                          "note": f"{steps - n_trig} steps with one live row, {n_trig} trigger steps "
+                                                  f"(up to {k + 1} live rows; second figure derived from the two run totals)"}
     if not args.no_sweep:
         sweep = {}
         for kk in sorted(set((1,) + tuple(wl.k_sweep))):
