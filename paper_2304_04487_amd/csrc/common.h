@@ -135,6 +135,7 @@ struct AttnArgs {
     int H, dh, max_seq;
     int n_chunks;           // launched chunks (upper bound over the batch)
     const int *rows_live;   // may be null: device int, rows 0 .. *rows_live of the (single) sequence carry tokens
+    const int *lo_from;     // may be null: [max_batch] device ints, positions below lo_from[slot] have all-zero lo planes (imported bf16 caches)
     int n_rblocks;          // row blocks per sequence (set by the launcher)
     float scale;
     float *po, *pm, *pl;    // partials

@@ -866,12 +866,11 @@ __device__ __forceinline__ void loads_stay_above() { asm volatile("" ::: "memory
 // are merged in wave order, and the chunk's partial is written for the combine kernel.  Which
 // keys a row sees, and in which order they are reduced, is a function of absolute positions only.
 template <int DH, int NTQ, bool KVS, bool LIVE>
-__global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
+__device__ __forceinline__ void attn_chunk_body(const AttnArgs &a, float (&sm)[4][NTQ * 16], float (&sl)[4][NTQ * 16],
+                                                float (&so)[4][NTQ * 16][DH + 4]) {
     constexpr int KSTEPS = DH / 32;   // MFMA k-steps of a q.k dot product
     constexpr int DT = DH / 16;       // 16-feature tiles of the head dimension
     constexpr int RQ = NTQ * 16;
-    __shared__ float sm[4][RQ], sl[4][RQ];
-    __shared__ float so[4][RQ][DH + 4];
 
     const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z / a.n_rblocks, rb = blockIdx.z % a.n_rblocks;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -1041,6 +1040,24 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
         a.pm[pbase + j] = M;
         a.pl[pbase + j] = L;
     }
+}
+
+// LOSKIP (batched steps on caches with hi + lo planes): positions below lo_from[slot] were imported
+// as bf16 values -- their lo planes hold zeros -- so a chunk that lies entirely below it runs the
+// single-plane form of the body: half the K/V bytes, the same sums (the skipped terms are zeros).
+template <int DH, int NTQ, bool KVS, bool LIVE, bool LOSKIP = false>
+__global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
+    constexpr int RQ = NTQ * 16;
+    __shared__ float sm[4][RQ], sl[4][RQ];
+    __shared__ float so[4][RQ][DH + 4];
+    if (KVS && LOSKIP) {
+        const int slot = a.slot_const >= 0 ? a.slot_const : a.batch_slots[blockIdx.z / a.n_rblocks];
+        if ((int)(blockIdx.x + 1) * ATTN_CHUNK <= a.lo_from[slot]) {     // uniform for the workgroup
+            attn_chunk_body<DH, NTQ, false, LIVE>(a, sm, sl, so);
+            return;
+        }
+    }
+    attn_chunk_body<DH, NTQ, KVS, LIVE>(a, sm, sl, so);
 }
 
 // merges the chunk partials of one (row, head): out = sum_c e^{m_c - M} O_c / sum_c e^{m_c - M} l_c,
@@ -1283,6 +1300,10 @@ static void launch_attn_dh(const AttnArgs &a0, hipStream_t st) {
         if (ntq == 1) hipLaunchKernelGGL((attn_bf16_kernel<DH, 1, KVS, true>), grid, dim3(256), 0, st, a);
         else if (ntq == 2) hipLaunchKernelGGL((attn_bf16_kernel<DH, 2, KVS, true>), grid, dim3(256), 0, st, a);
         else hipLaunchKernelGGL((attn_bf16_kernel<DH, 3, KVS, true>), grid, dim3(256), 0, st, a);
+    } else if (KVS && a.slot_const < 0 && a.lo_from != nullptr) {   // several sequences: their caches may have been imported
+        if (ntq == 1) hipLaunchKernelGGL((attn_bf16_kernel<DH, 1, KVS, false, true>), grid, dim3(256), 0, st, a);
+        else if (ntq == 2) hipLaunchKernelGGL((attn_bf16_kernel<DH, 2, KVS, false, true>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((attn_bf16_kernel<DH, 3, KVS, false, true>), grid, dim3(256), 0, st, a);
     } else if (ntq == 1) hipLaunchKernelGGL((attn_bf16_kernel<DH, 1, KVS, false>), grid, dim3(256), 0, st, a);
     else if (ntq == 2) hipLaunchKernelGGL((attn_bf16_kernel<DH, 2, KVS, false>), grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL((attn_bf16_kernel<DH, 3, KVS, false>), grid, dim3(256), 0, st, a);

@@ -76,7 +76,13 @@ struct llma_ctx {
     int *gen_counters = nullptr;                  // n_out[max_batch], n_steps[max_batch], cur[max_batch][2], prefill base
     int cap_prompt = 0, cap_ref = 0, cap_refdoc = 0, cap_docs = 0, cap_y = 0, cap_trace = 0;
 
-    std::vector<int> T_host, pending_host, import_mask_layers;
+    std::vector<int> T_host, pending_host;
+    // Caches imported as bf16 values have all-zero lo planes: positions below lo_from[slot] (device
+    // ints, host mirror) need no lo reads.  It is set when all layers of a slot have been imported
+    // with one length and nothing was computed on the slot in between (imp_len records the lengths
+    // since then, -1 = none); steps only ever write at positions >= T >= lo_from, reset clears it.
+    std::vector<int> lo_from_host, imp_len;
+    int *lo_from = nullptr;
     float *logits_dump = nullptr;
     int dump_rows = 0;
     int opt_split = 1, opt_timing = 0, opt_graph = 1;
@@ -292,7 +298,10 @@ static int create_impl(llma_ctx *c, const llma_weights *w) {
     ALLOC(c, c->gen_counters, (size_t)(4 * g.max_batch + 4) * 4);
     c->T_host.assign(g.max_batch, 0);
     c->pending_host.assign(g.max_batch, -1);
-    c->import_mask_layers.assign(g.max_batch, 0);
+    c->lo_from_host.assign(g.max_batch, 0);
+    c->imp_len.assign((size_t)g.max_batch * g.n_layers, -1);
+    ALLOC(c, c->lo_from, g.max_batch * 4);
+    HIP_TRY(c, hipMemsetAsync(c->lo_from, 0, g.max_batch * 4, c->st));
     HIP_TRY(c, hipStreamCreateWithFlags(&c->cap_st, hipStreamNonBlocking));
     HIP_TRY(c, hipHostMalloc((void **)&c->pin_counts, (size_t)2 * g.max_batch * sizeof(int), hipHostMallocDefault));
     HIP_TRY(c, hipEventCreateWithFlags(&c->cnt_ev[0], hipEventDisableTiming));
@@ -407,6 +416,7 @@ static int forward_bf16(llma_ctx *c, int n_seqs, int m, int n_chunks, bool lm_he
     AttnArgs aa{};
     aa.Qhi = c->q; aa.Qlo = c->q_lo; aa.T = c->s.T; aa.batch_slots = c->s.batch_slots; aa.slot_const = n_seqs == 1 ? slot : -1; aa.n_seqs = n_seqs; aa.m = m; aa.H = H; aa.dh = dh;
     aa.rows_live = c->rows_live;
+    aa.lo_from = c->kv_split ? c->lo_from : nullptr;
     aa.max_seq = c->seq_cap; aa.n_chunks = n_chunks; aa.scale = 1.0f / sqrtf((float)dh);
     aa.po = c->po; aa.pm = c->pm; aa.pl = c->pl; aa.out_hi = c->att_hi; aa.out_lo = c->att_lo; aa.out_KSp = ksp_d;
     for (int l = 0; l < L; ++l) {
@@ -531,8 +541,13 @@ static int check_slot(llma_ctx *c, int seq, const char *who) {
 static int push_state(llma_ctx *c, int seq) {       // host mirror -> device
     HIP_TRY(c, hipMemcpyAsync(c->s.T + seq, &c->T_host[seq], 4, hipMemcpyHostToDevice, c->st));
     HIP_TRY(c, hipMemcpyAsync(c->s.pending + seq, &c->pending_host[seq], 4, hipMemcpyHostToDevice, c->st));
+    HIP_TRY(c, hipMemcpyAsync(c->lo_from + seq, &c->lo_from_host[seq], 4, hipMemcpyHostToDevice, c->st));
     HIP_TRY(c, hipStreamSynchronize(c->st));
     return LLMA_OK;
+}
+// something is about to be computed on the slot: the record of imported lengths no longer describes a pure import
+static void forget_imports(llma_ctx *c, int seq) {
+    for (int l = 0; l < c->cfg.n_layers; ++l) c->imp_len[(size_t)seq * c->cfg.n_layers + l] = -1;
 }
 
 extern "C" int llma_reset(llma_ctx *c, int32_t seq) {
@@ -540,7 +555,8 @@ extern "C" int llma_reset(llma_ctx *c, int32_t seq) {
     if (rc) return rc;
     c->T_host[seq] = 0;
     c->pending_host[seq] = -1;
-    c->import_mask_layers[seq] = 0;
+    c->lo_from_host[seq] = 0;
+    forget_imports(c, seq);
     return push_state(c, seq);
 }
 
@@ -580,8 +596,12 @@ extern "C" int llma_kv_import(llma_ctx *c, int32_t seq, int32_t layer, const voi
         else launch_kv_import_f32(k, v, kc, vc, g.n_heads, len, g.head_dim, c->seq_cap, c->st);
     }
     HIP_TRY(c, hipGetLastError());
+    c->imp_len[(size_t)seq * g.n_layers + layer] = len;
     if (layer == g.n_layers - 1) {
         c->T_host[seq] = len;
+        bool all = c->kv_split != 0;
+        for (int l = 0; l < g.n_layers; ++l) all = all && c->imp_len[(size_t)seq * g.n_layers + l] == len;
+        c->lo_from_host[seq] = all ? len : 0;
         return push_state(c, seq);
     }
     return LLMA_OK;
@@ -627,6 +647,7 @@ extern "C" int llma_prefill(llma_ctx *c, int32_t seq, const int32_t *prompt, int
     if ((rc = check_tokens(c, prompt, len, "llma_prefill"))) return rc;
     if ((rc = ensure_cap(c, &c->gen_prompt, &c->cap_prompt, len))) return rc;
     HIP_TRY(c, hipMemcpyAsync(c->gen_prompt, prompt, (size_t)len * 4, hipMemcpyHostToDevice, c->st));
+    forget_imports(c, seq);
     if ((rc = prefill_rows(c, seq, len - 1))) return rc;
     c->pending_host[seq] = prompt[len - 1];
     HIP_TRY(c, hipMemcpyAsync(c->s.pending + seq, &c->pending_host[seq], 4, hipMemcpyHostToDevice, c->st));
@@ -706,6 +727,7 @@ extern "C" int llma_verify_step_batch(llma_ctx *c, int32_t n_seqs, const int32_t
     HIP_TRY(c, hipMemcpyAsync(c->s.batch_slots, seqs, (size_t)n_seqs * 4, hipMemcpyHostToDevice, st));
     HIP_TRY(c, hipMemcpyAsync(c->s.keff, keff.data(), (size_t)n_seqs * 4, hipMemcpyHostToDevice, st));
     if (k > 0) HIP_TRY(c, hipMemcpyAsync(c->s.draft, dr.data(), (size_t)n_seqs * mk * 4, hipMemcpyHostToDevice, st));
+    for (int b = 0; b < n_seqs; ++b) forget_imports(c, seqs[b]);
     int rc = run_step(c, STEP_VERIFY, n_seqs, m, t_max, n_seqs == 1 ? seqs[0] : 0);
     if (rc) return rc;
     std::vector<int> nacc(n_seqs), nxt(n_seqs), em((size_t)n_seqs * (mk + 1));
@@ -817,7 +839,8 @@ extern "C" int llma_generate_batch(llma_ctx *c, int32_t n_seqs, const int32_t *s
         HIP_TRY(c, hipMemcpyAsync(c->gen_prompt, prompt, (size_t)plen * 4, hipMemcpyHostToDevice, st));
         c->T_host[seq] = 0;
         c->pending_host[seq] = prompt[plen - 1];
-        c->import_mask_layers[seq] = 0;
+        c->lo_from_host[seq] = 0;
+        forget_imports(c, seq);
         if ((rc = push_state(c, seq))) return rc;
         if ((rc = prefill_rows(c, seq, plen - 1))) return rc;
         HIP_TRY(c, hipStreamSynchronize(st));                   // gen_prompt is reused by the next sequence

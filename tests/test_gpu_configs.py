@@ -342,6 +342,53 @@ def test_batched_verify_step_on_imported_caches(llma, kv_split):
     ctx.close()
 
 
+def test_batched_step_after_import_and_prompt_rows(llma):
+    """Imported bf16 caches have all-zero lo planes, which batched steps do not read for chunks that lie
+    entirely inside the imported part.  Rows computed on top of an import (a 60-row prompt pass on one
+    slot, a verification step on both) have lo planes and must be read in full: two batched steps
+    after import + prompt rows against the oracle."""
+    cfg = synth.ModelCfg("vb2", 3, 512, 4, 128, 1024, 4096, "bf16")
+    w = synth.make_weights(cfg, 9)
+    om = OracleModel(cfg, w)
+    lens, slots, k = [200, 140], [1, 3], 4
+    ctx = llma.Context(cfg, w, max_seq=400, max_batch=4, max_k=8, kv_split=True)
+    ctx.enable_logits_dump(2 * (k + 1))
+    caches, T, pend = [], [], []
+    for b, (slot, Tb) in enumerate(zip(slots, lens)):
+        cache = om.new_cache(400)
+        for l in range(cfg.n_layers):
+            kk, vv = synth.make_kv_fill(cfg, 300 + b, 1, Tb, l)
+            cache.k[l][:, :Tb] = synth.bf16_to_f32(kk[0]).astype(np.float64)
+            cache.v[l][:, :Tb] = synth.bf16_to_f32(vv[0]).astype(np.float64)
+            ctx.kv_import(slot, l, torch.from_numpy(kk[0]).cuda(), torch.from_numpy(vv[0]).cuda(), Tb)
+        caches.append(cache); T.append(Tb); pend.append(11 + b)
+        ctx.set_pending(11 + b, slot)
+    more = synth.uniform_tokens(5, 77, 61, cfg.vocab)
+    ctx.prefill(more, slots[0])                                  # 60 rows on top of the imported 200
+    om.forward(more[:-1], caches[0], T[0])
+    T[0] += 60; pend[0] = int(more[-1])
+    assert ctx.get_state(slots[0]) == (T[0], pend[0])
+    for step in range(2):
+        drafts, wants, accs = [], [], []
+        for b in range(2):
+            d = synth.uniform_tokens(40 + step, b, k, cfg.vocab).tolist()
+            want = om.forward([pend[b]] + d, caches[b], T[b])
+            o = argmax_tokens(want)
+            a = 0
+            while a < k and o[a] == d[a]:
+                a += 1
+            drafts.append(d); wants.append(want); accs.append((a, int(o[a])))
+        na, nxt, _ = ctx.verify_step_batch(slots, drafts)
+        got = ctx.logits(2 * (k + 1)).reshape(2, k + 1, cfg.vocab)
+        for b in range(2):
+            check_logits(got[b], wants[b], f"import+prompt rows, step {step} seq {b}")
+            if top2_gap(wants[b][accs[b][0]]) > ATOL + RTOL * abs(float(wants[b][accs[b][0]].max())):
+                assert (int(na[b]), int(nxt[b])) == accs[b], (step, b)
+            T[b] += int(na[b]) + 1; pend[b] = int(nxt[b])
+            assert ctx.get_state(slots[b]) == (T[b], pend[b])
+    ctx.close()
+
+
 # --------------------------------------------------------------------------- the verify-step microbenchmark at full size
 @pytest.mark.timeout(900)
 def test_verify_microbench_full_size(llma):
