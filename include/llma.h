@@ -102,7 +102,10 @@ int llma_set_pending(llma_ctx *ctx, int32_t seq, int32_t token);
 /* Replaces layer `layer` of slot `seq`'s KV cache by caller data and sets T = len once the
  * last layer has been imported.  k, v: DEVICE pointers, plain layout [n_heads, len,
  * head_dim] in the configured dtype; keys are taken as already rotated.  Used to start
- * the verify-step microbenchmark from a given cache without running a prefill. */
+ * the verify-step microbenchmark from a given cache without running a prefill.  With
+ * kv_split the imported values fill the hi planes exactly and the lo planes with zeros;
+ * when all layers of a slot have been imported with one len (and nothing was computed on
+ * the slot in between), batched steps do not read the lo planes below that position. */
 int llma_kv_import(llma_ctx *ctx, int32_t seq, int32_t layer, const void *k, const void *v, int32_t len);
 
 /* --- the three calls of the method ---------------------------------------------------- */

@@ -865,12 +865,18 @@ __device__ __forceinline__ void loads_stay_above() { asm volatile("" ::: "memory
 // softmax statistics per query row, O^T = V^T . P^T (again hi/lo).  The four waves' (max, sum, O)
 // are merged in wave order, and the chunk's partial is written for the combine kernel.  Which
 // keys a row sees, and in which order they are reduced, is a function of absolute positions only.
-template <int DH, int NTQ, bool KVS, bool LIVE>
+// COMPACT (three row tiles, at most ATTN_COMPACT_ROWS rows: the 33 rows per sequence of k = 32): the
+// merge buffer holds only that many rows, every row tile is published as soon as it is done (one
+// tile of accumulators in registers at a time) and the registers are capped, so that two workgroups
+// fit a compute unit like they do with one or two row tiles.
+#define ATTN_COMPACT_ROWS 36
+template <int DH, int NTQ, bool KVS, bool LIVE, bool COMPACT = false>
 __device__ __forceinline__ void attn_chunk_body(const AttnArgs &a, float (&sm)[4][NTQ * 16], float (&sl)[4][NTQ * 16],
-                                                float (&so)[4][NTQ * 16][DH + 4]) {
+                                                float (&so)[4][COMPACT ? ATTN_COMPACT_ROWS : NTQ * 16][DH + 4]) {
     constexpr int KSTEPS = DH / 32;   // MFMA k-steps of a q.k dot product
     constexpr int DT = DH / 16;       // 16-feature tiles of the head dimension
     constexpr int RQ = NTQ * 16;
+    constexpr int OQ = COMPACT ? 1 : NTQ;                      // row tiles of accumulators held at once
 
     const int c = blockIdx.x, h = blockIdx.y, b = blockIdx.z / a.n_rblocks, rb = blockIdx.z % a.n_rblocks;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -931,19 +937,39 @@ __device__ __forceinline__ void attn_chunk_body(const AttnArgs &a, float (&sm)[4
     const bool active = key0 < kv_len;                  // uniform for the wave
 
     float mrow[NTQ], lrow[NTQ];
-    f32x4 o[NTQ][DT];
+    f32x4 o[OQ][DT];
 #pragma unroll
     for (int q = 0; q < NTQ; ++q) {
         mrow[q] = LLMA_NEG_INF;
         lrow[q] = 0.f;
+    }
+#pragma unroll
+    for (int q = 0; q < OQ; ++q)
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) o[q][dt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    // every wave publishes (max, sum, O) of a row tile for the merge below
+    auto publish = [&](int q, const f32x4 (&oq)[DT]) {
+        float l = lrow[q];
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        if (g == 0) { sm[wave][q * 16 + n] = mrow[q]; sl[wave][q * 16 + n] = l; }
+        if (!COMPACT || q * 16 + n < ATTN_COMPACT_ROWS)
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) *(f32x4 *)&so[wave][q * 16 + n][dt * 16 + 4 * g] = oq[dt];
+    };
+    if (COMPACT && !active) {
+#pragma unroll
+        for (int q = 0; q < NTQ; ++q) publish(q, o[0]);         // (zeros)
     }
 
     if (active) {
 #pragma unroll
         for (int q = 0; q < NTQ; ++q) {
-            if (LIVE && q > 0 && j0 + q * 16 >= m_live) continue;   // uniform: no live row in this tile
+            const int oi = COMPACT ? 0 : q;
+            if (LIVE && q > 0 && j0 + q * 16 >= m_live) {           // uniform: no live row in this tile
+                if (COMPACT) publish(q, o[0]);                      // (zeros: o[0] is cleared after every tile)
+                continue;
+            }
             const int j = j0 + q * 16 + n;
             const bool valid = j < m_live;
             const int rpos = valid ? T + j : -1;
@@ -994,23 +1020,23 @@ __device__ __forceinline__ void attn_chunk_body(const AttnArgs &a, float (&sm)[4
             const u32x4 pl = (u32x4){l0[0], l0[1], l1[0], l1[1]};
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) {
-                o[q][dt] = mfma16x16x32(va[dt], ph, o[q][dt]);
-                o[q][dt] = mfma16x16x32(va[dt], pl, o[q][dt]);
-                if (KVS) o[q][dt] = mfma16x16x32(vb[dt], ph, o[q][dt]);
+                o[oi][dt] = mfma16x16x32(va[dt], ph, o[oi][dt]);
+                o[oi][dt] = mfma16x16x32(va[dt], pl, o[oi][dt]);
+                if (KVS) o[oi][dt] = mfma16x16x32(vb[dt], ph, o[oi][dt]);
+            }
+            if (COMPACT) {
+                publish(q, o[0]);
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) o[0][dt] = (f32x4){0.f, 0.f, 0.f, 0.f};
             }
         }
     }
 
     // ---- merge the four waves in wave order: every wave publishes (max, sum, O), then all
     //      threads add the four contributions e^{m_w - M} O_w of an output element in wave order
+    if (!COMPACT) {
 #pragma unroll
-    for (int q = 0; q < NTQ; ++q) {
-        float l = lrow[q];
-        l += __shfl_xor(l, 16);
-        l += __shfl_xor(l, 32);
-        if (g == 0) { sm[wave][q * 16 + n] = mrow[q]; sl[wave][q * 16 + n] = l; }
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) *(f32x4 *)&so[wave][q * 16 + n][dt * 16 + 4 * g] = o[q][dt];
+        for (int q = 0; q < NTQ; ++q) publish(q, o[COMPACT ? 0 : q]);
     }
     __syncthreads();
     const size_t pbase = (((size_t)b * a.H + h) * a.n_chunks + c) * ((size_t)a.n_rblocks * RQ) + j0;
@@ -1045,19 +1071,19 @@ __device__ __forceinline__ void attn_chunk_body(const AttnArgs &a, float (&sm)[4
 // LOSKIP (batched steps on caches with hi + lo planes): positions below lo_from[slot] were imported
 // as bf16 values -- their lo planes hold zeros -- so a chunk that lies entirely below it runs the
 // single-plane form of the body: half the K/V bytes, the same sums (the skipped terms are zeros).
-template <int DH, int NTQ, bool KVS, bool LIVE, bool LOSKIP = false>
-__global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a) {
+template <int DH, int NTQ, bool KVS, bool LIVE, bool LOSKIP = false, bool COMPACT = false>
+__global__ __launch_bounds__(256, (COMPACT ? 2 : 1)) void attn_bf16_kernel(AttnArgs a) {
     constexpr int RQ = NTQ * 16;
     __shared__ float sm[4][RQ], sl[4][RQ];
-    __shared__ float so[4][RQ][DH + 4];
+    __shared__ float so[4][COMPACT ? ATTN_COMPACT_ROWS : RQ][DH + 4];
     if (KVS && LOSKIP) {
         const int slot = a.slot_const >= 0 ? a.slot_const : a.batch_slots[blockIdx.z / a.n_rblocks];
         if ((int)(blockIdx.x + 1) * ATTN_CHUNK <= a.lo_from[slot]) {     // uniform for the workgroup
-            attn_chunk_body<DH, NTQ, false, LIVE>(a, sm, sl, so);
+            attn_chunk_body<DH, NTQ, false, LIVE, COMPACT>(a, sm, sl, so);
             return;
         }
     }
-    attn_chunk_body<DH, NTQ, KVS, LIVE>(a, sm, sl, so);
+    attn_chunk_body<DH, NTQ, KVS, LIVE, COMPACT>(a, sm, sl, so);
 }
 
 // merges the chunk partials of one (row, head): out = sum_c e^{m_c - M} O_c / sum_c e^{m_c - M} l_c,
@@ -1303,6 +1329,7 @@ static void launch_attn_dh(const AttnArgs &a0, hipStream_t st) {
     } else if (KVS && a.slot_const < 0 && a.lo_from != nullptr) {   // several sequences: their caches may have been imported
         if (ntq == 1) hipLaunchKernelGGL((attn_bf16_kernel<DH, 1, KVS, false, true>), grid, dim3(256), 0, st, a);
         else if (ntq == 2) hipLaunchKernelGGL((attn_bf16_kernel<DH, 2, KVS, false, true>), grid, dim3(256), 0, st, a);
+        else if (a.m <= ATTN_COMPACT_ROWS) hipLaunchKernelGGL((attn_bf16_kernel<DH, 3, KVS, false, true, true>), grid, dim3(256), 0, st, a);
         else hipLaunchKernelGGL((attn_bf16_kernel<DH, 3, KVS, false, true>), grid, dim3(256), 0, st, a);
     } else if (ntq == 1) hipLaunchKernelGGL((attn_bf16_kernel<DH, 1, KVS, false>), grid, dim3(256), 0, st, a);
     else if (ntq == 2) hipLaunchKernelGGL((attn_bf16_kernel<DH, 2, KVS, false>), grid, dim3(256), 0, st, a);

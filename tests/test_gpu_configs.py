@@ -342,16 +342,18 @@ def test_batched_verify_step_on_imported_caches(llma, kv_split):
     ctx.close()
 
 
-def test_batched_step_after_import_and_prompt_rows(llma):
+@pytest.mark.parametrize("k", [4, 32], ids=["k4", "k32"])
+def test_batched_step_after_import_and_prompt_rows(llma, k):
     """Imported bf16 caches have all-zero lo planes, which batched steps do not read for chunks that lie
     entirely inside the imported part.  Rows computed on top of an import (a 60-row prompt pass on one
     slot, a verification step on both) have lo planes and must be read in full: two batched steps
-    after import + prompt rows against the oracle."""
+    after import + prompt rows against the oracle (k = 32: 33 rows per sequence, the three-row-tile
+    form of the attention kernel with its small merge buffer)."""
     cfg = synth.ModelCfg("vb2", 3, 512, 4, 128, 1024, 4096, "bf16")
     w = synth.make_weights(cfg, 9)
     om = OracleModel(cfg, w)
-    lens, slots, k = [200, 140], [1, 3], 4
-    ctx = llma.Context(cfg, w, max_seq=400, max_batch=4, max_k=8, kv_split=True)
+    lens, slots = [200, 140], [1, 3]
+    ctx = llma.Context(cfg, w, max_seq=400, max_batch=4, max_k=32, kv_split=True)
     ctx.enable_logits_dump(2 * (k + 1))
     caches, T, pend = [], [], []
     for b, (slot, Tb) in enumerate(zip(slots, lens)):
