@@ -15,6 +15,11 @@ small-configuration parity test), float32 permitted for the 7B/13B shapes where 
 copies of the weights would not fit in host memory.  The arg-max decision is always taken
 on logits rounded to float32, lowest token id winning exact ties, because that is the
 precision the GPU path decides in.
+
+Where even float32 copies do not fit (the 13B shape: 51 GB), `lazy=True` keeps the layers'
+matrices in the form they arrive in (bfloat16 bit patterns) and widens one layer at a time
+inside forward(); the arithmetic is the same, only the moment of the (exact) format
+conversion differs.
 """
 from __future__ import annotations
 
@@ -24,8 +29,25 @@ import numpy as np
 def _widen(a: np.ndarray, dtype) -> np.ndarray:
     """Weights arrive as float32 or as bfloat16 bit patterns (uint16); both widen exactly."""
     if a.dtype == np.uint16:
-        a = (a.astype(np.uint32) << 16).view(np.float32)
+        # the 16 stored bits are the upper half of the float32 pattern
+        return np.left_shift(a, 16, dtype=np.uint32, casting="unsafe").view(np.float32).astype(dtype, copy=False)
     return a.astype(dtype)
+
+
+class _LayersWidenedOnDemand:
+    """The per-layer weight dicts of a model whose matrices stay in their storage format;
+    iterating yields one layer at a time, widened to the arithmetic dtype (and dropped
+    again when the next one is asked for)."""
+
+    def __init__(self, raw_layers, dtype):
+        self.raw, self.dtype = raw_layers, dtype
+
+    def __len__(self):
+        return len(self.raw)
+
+    def __iter__(self):
+        for lw in self.raw:
+            yield {k: (_widen(v, self.dtype) if v.ndim == 2 else v.astype(self.dtype)) for k, v in lw.items()}
 
 
 def rmsnorm(x: np.ndarray, g: np.ndarray, eps: float) -> np.ndarray:
@@ -61,14 +83,16 @@ class KVCache:
 
 
 class OracleModel:
-    def __init__(self, cfg, weights: dict, dtype=np.float64):
+    def __init__(self, cfg, weights: dict, dtype=np.float64, lazy: bool = False):
         self.cfg = cfg
         self.dtype = dtype
         self.embed = _widen(weights["embed"], dtype)
         self.lm_head = _widen(weights["lm_head"], dtype)
         self.final_norm = weights["final_norm"].astype(dtype)
-        self.layers = [{k: (_widen(v, dtype) if v.ndim == 2 else v.astype(dtype))
-                        for k, v in lw.items()} for lw in weights["layers"]]
+        if lazy:
+            self.layers = _LayersWidenedOnDemand(weights["layers"], dtype)
+        else:
+            self.layers = list(_LayersWidenedOnDemand(weights["layers"], dtype))
 
     def new_cache(self, capacity: int) -> KVCache:
         c = self.cfg

@@ -12,7 +12,7 @@ import torch
 
 import synth
 from oracle import OracleModel, CachedLLM, greedy_decode, llma_decode, infer_decoding_sequence
-from oracle.model import rmsnorm, rope, silu, argmax_tokens
+from oracle.model import rmsnorm, rope, silu, argmax_tokens, top2_gap
 
 MINI = synth.ModelCfg("mini", 3, 64, 4, 16, 96, 97, "bf16")
 
@@ -225,3 +225,36 @@ def test_argmax_lowest_index_on_ties():
     # a float64 difference below float32 resolution is a tie in the deciding precision
     lg = np.array([[1.0, 1.0 + 1e-12]])
     assert argmax_tokens(lg).tolist() == [0]
+
+
+def test_top2_gap_hand_rows_and_sorted_definition():
+    """top2_gap decides when a GPU / oracle token mismatch counts as a near-tie, so it is pinned
+    on its own: hand rows (exact tie -> 0, the runner-up may sit before or after the maximum,
+    negative rows, float32 input) and the definition via a full sort on random rows."""
+    assert top2_gap(np.array([1.0, 5.0, 2.0, 4.5])) == 0.5
+    assert top2_gap(np.array([4.5, 1.0, 5.0])) == 0.5
+    assert top2_gap(np.array([3.0, 3.0, -1.0])) == 0.0
+    assert top2_gap(np.array([7.0, 7.0])) == 0.0
+    assert top2_gap(np.array([-9.0, -2.0, -2.25, -30.0])) == 0.25
+    assert top2_gap(np.array([0.0, 1e-3], dtype=np.float32)) == pytest.approx(1e-3, rel=1e-6)
+    assert top2_gap(np.array([1.0, 1.0 + 1e-12])) == pytest.approx(1e-12, rel=1e-3)    # no rounding to float32 here
+    rng = np.random.default_rng(5)
+    for n in (2, 3, 17, 32000):
+        for _ in range(20):
+            row = rng.standard_normal(n) * 1.3
+            if n > 3:
+                row[rng.integers(n)] = row.max() - rng.random() * 1e-3               # a close runner-up
+            srt = np.sort(row)
+            assert top2_gap(row) == pytest.approx(srt[-1] - srt[-2], abs=1e-15)
+            assert top2_gap(row) >= 0.0
+
+
+def test_layers_widened_on_demand_give_identical_logits():
+    """lazy=True only moves the exact bf16 -> float conversion into forward()."""
+    w = synth.make_weights(MINI, 31, gain_jitter=0.2)
+    toks = list(range(3, 30))
+    a, b = OracleModel(MINI, w, np.float32), OracleModel(MINI, w, np.float32, lazy=True)
+    ca, cb = a.new_cache(40), b.new_cache(40)
+    assert len(cb.k) == MINI.n_layers
+    for T0, T1 in ((0, 20), (20, 27)):
+        assert np.array_equal(a.forward(toks[T0:T1], ca, T0), b.forward(toks[T0:T1], cb, T0))
