@@ -9,7 +9,7 @@ void launch_kv_import_bf16(const void *k, const void *v, void *kh, void *kl, voi
                            int max_seq, hipStream_t st);
 void launch_embed_prep_bf16(const void *embed, const int *row_tok, const float *gain, float *h, void *nx_hi, void *nx_lo,
                             float *ssq_out, int R, int d, int KSp, hipStream_t st);
-void launch_gemm_bf16(const GemmArgs &a, hipStream_t st);
+bool launch_gemm_bf16(const GemmArgs &a, hipStream_t st);   // false (nothing launched) unless 1 <= rows <= 48
 void launch_gemm_panel_bf16(const GemmArgs &a, hipStream_t st);
 void launch_rstd_rows(const float *ssq, int ssq_tiles, float eps, float *rstd, int rows, hipStream_t st);
 void launch_attn_bf16(const AttnArgs &a, hipStream_t st);
@@ -54,10 +54,11 @@ void launch_rope_kv_f32(const float *qkv, const StepState &s, const float *cs_ta
                         int R, int H, int dh, int max_seq, hipStream_t st);
 // final arg max over the per-row partials, then prefix accept + KV truncate + bookkeeping
 void launch_argmax_accept(const float *pval, const int *pidx, int n_part, const StepState &s, int n_seqs, int m,
-                          int max_k, const GenState *gen /*device array [n_seqs] or null*/, hipStream_t st);
+                          int max_k, int vocab, const GenState *gen /*device array [n_seqs] or null*/, hipStream_t st);
 // trigger scan for each sequence being generated (gen_dev[b]); fills keff[b] / draft[b][:]
 void launch_trigger(const GenState *gen_dev, const StepState &s, int n_seqs, int max_k, hipStream_t st);
-// stateless trigger on device arrays (llma_find_trigger): result[0..2] = matched, doc, pos
+// stateless trigger on device arrays (llma_find_trigger): result[0..2] = matched, doc, pos; with
+// check_offsets the kernel itself validates doc_offsets and reports (-1, -1, -1) for a bad list
 void launch_trigger_plain(const int *y, int y_len, const int *ref, const int *doc_offsets, const int *ref_doc,
-                          int ref_len, int n, int *result, hipStream_t st);
+                          int ref_len, int n_docs, int n, int *result, bool check_offsets, hipStream_t st);
 void launch_fill_ref_doc(const int *doc_offsets, int n_docs, int *ref_doc, int ref_len, hipStream_t st);

@@ -14,8 +14,22 @@
 // processed in a one-row step.
 #include <stdlib.h>
 
+#include <atomic>
+
 #include "common.h"
 #include "kernels.h"
+
+// Kernels that use more than 64 KB of dynamic LDS need the limit raised once per device.  `done`
+// (one per kernel instantiation) holds a bit per device id; concurrent first calls may both set the
+// attribute, which is harmless.
+static void allow_full_lds(const void *kernel, std::atomic<uint64_t> &done) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev > 63) dev = 0;
+    const uint64_t bit = 1ull << dev;
+    if (done.load(std::memory_order_acquire) & bit) return;
+    (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    done.fetch_or(bit, std::memory_order_release);
+}
 
 // =============================================================================================
 // weight re-tiling: row-major [N][K] bf16 -> 1 KiB MFMA A-operand blocks (see common.h)
@@ -472,12 +486,12 @@ static void launch_tilek(const GemmArgs &a, hipStream_t st) {
     const size_t lds = (size_t)S * FT * TILES * NT * 1024 + 256;
     dim3 grid((p.tasks + FT - 1) / FT), block(W * 64);
     if (a.split) {
-        static bool attr_done = false;
-        if (!attr_done) { (void)hipFuncSetAttribute((const void *)gemm_tilek_bf16<NT, EPI, true, FT>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); attr_done = true; }
+        static std::atomic<uint64_t> done{0};
+        allow_full_lds((const void *)gemm_tilek_bf16<NT, EPI, true, FT>, done);
         hipLaunchKernelGGL((gemm_tilek_bf16<NT, EPI, true, FT>), grid, block, lds, st, a);
     } else {
-        static bool attr_done = false;
-        if (!attr_done) { (void)hipFuncSetAttribute((const void *)gemm_tilek_bf16<NT, EPI, false, FT>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); attr_done = true; }
+        static std::atomic<uint64_t> done{0};
+        allow_full_lds((const void *)gemm_tilek_bf16<NT, EPI, false, FT>, done);
         hipLaunchKernelGGL((gemm_tilek_bf16<NT, EPI, false, FT>), grid, block, lds, st, a);
     }
 }
@@ -749,8 +763,8 @@ static void launch_panel_cfg(const GemmArgs &a, hipStream_t st) {
     GemmArgs a2 = a;
     a2.panel_rb = (a.rows + 16 * RT - 1) / (16 * RT);
     dim3 grid(FB * a2.panel_rb, a.ksplit > 1 ? a.ksplit : 1), block(WV * 64);
-    static bool attr_done = false;
-    if (!attr_done) { (void)hipFuncSetAttribute((const void *)gemm_panel_bf16<RT, EPI, FT, WV>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); attr_done = true; }
+    static std::atomic<uint64_t> done{0};
+    allow_full_lds((const void *)gemm_panel_bf16<RT, EPI, FT, WV>, done);
     hipLaunchKernelGGL((gemm_panel_bf16<RT, EPI, FT, WV>), grid, block, lds, st, a2);
 }
 
@@ -802,29 +816,15 @@ void launch_gemm_panel_bf16(const GemmArgs &a, hipStream_t st) {
     }
 }
 
-// decoding-step GEMM: up to 48 rows (three row tiles) per launch (the callers send steps of more
-// rows to the panel kernel; should more arrive here, they are processed in blocks of 48)
-void launch_gemm_bf16(const GemmArgs &a0, hipStream_t st) {
-    const GemmPlan &p = a0.plan;
-    for (int r0 = 0; r0 < a0.rows; r0 += 48) {
-        GemmArgs a = a0;
-        const int rows = a0.rows - r0 < 48 ? a0.rows - r0 : 48;
-        const int t0 = r0 / 16;
-        a.rows = rows;
-        a.Xhi = (const bf16_t *)a0.Xhi + (size_t)t0 * p.KSp * 512;
-        a.Xlo = a0.Xlo ? (const bf16_t *)a0.Xlo + (size_t)t0 * p.KSp * 512 : nullptr;
-        if (a0.ssq_in) a.ssq_in = a0.ssq_in + (size_t)r0 * a0.ssq_tiles;
-        if (a0.out) a.out = a0.out + (size_t)r0 * p.N;
-        if (a0.nx_hi) { a.nx_hi = (bf16_t *)a0.nx_hi + (size_t)t0 * a0.nx_KSp * 512; a.nx_lo = (bf16_t *)a0.nx_lo + (size_t)t0 * a0.nx_KSp * 512; }
-        if (a0.ssq_out) a.ssq_out = a0.ssq_out + (size_t)r0 * (p.N / 16);
-        if (a0.act_hi) { a.act_hi = (bf16_t *)a0.act_hi + (size_t)t0 * a0.act_KSp * 512; a.act_lo = (bf16_t *)a0.act_lo + (size_t)t0 * a0.act_KSp * 512; }
-        if (a0.pval) { a.pval = a0.pval + (size_t)r0 * a0.n_part; a.pidx = a0.pidx + (size_t)r0 * a0.n_part; }
-        if (a0.row_pos) { a.row_pos = a0.row_pos + r0; a.row_slot = a0.row_slot + r0; a.row_cs = a0.row_cs + (size_t)r0 * a0.dh; }
-        if (a0.q_hi) { a.q_hi = (bf16_t *)a0.q_hi + (size_t)t0 * (a0.H * a0.dh / 32) * 512; a.q_lo = (bf16_t *)a0.q_lo + (size_t)t0 * (a0.H * a0.dh / 32) * 512; }
-        if (rows <= 16) launch_gemm_nt<1>(a, st);
-        else if (rows <= 32) launch_gemm_nt<2>(a, st);
-        else launch_gemm_nt<3>(a, st);
-    }
+// decoding-step GEMM: one launch for up to 48 rows (three row tiles).  More rows are refused (false,
+// nothing launched): every workgroup re-reads all rows' operands, so larger steps belong to the panel
+// kernel, and processing them here in blocks would stream the weights once per block.
+bool launch_gemm_bf16(const GemmArgs &a, hipStream_t st) {
+    if (a.rows < 1 || a.rows > 48) return false;
+    if (a.rows <= 16) launch_gemm_nt<1>(a, st);
+    else if (a.rows <= 32) launch_gemm_nt<2>(a, st);
+    else launch_gemm_nt<3>(a, st);
+    return true;
 }
 
 // how a [N][K] weight matrix is cut into work for the tile-K kernel: three feature tiles per

@@ -116,7 +116,7 @@ void launch_rope_kv_f32(const float *qkv, const StepState &s, const float *cs_ta
 // of the a accepted drafts (T += a + 1; rows beyond are overwritten by the next step), and
 // o_a becomes the pending token.
 __global__ __launch_bounds__(256) void argmax_accept_kernel(const float *__restrict__ pval, const int *__restrict__ pidx,
-                                                            int n_part, StepState s, int m, int max_k, const GenState *gen) {
+                                                            int n_part, StepState s, int m, int max_k, int vocab, const GenState *gen) {
     __shared__ int o[40];
     const int b = blockIdx.x;
     if (gen != nullptr) gen += b;                                // llma_generate: one GenState per sequence of the batch
@@ -147,6 +147,9 @@ __global__ __launch_bounds__(256) void argmax_accept_kernel(const float *__restr
             int oi = __shfl_xor(bi, off);
             if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
         }
+        // a row without any comparable logit (all NaN: reachable through imported caches or weights that
+        // hold non-finite values) must still yield a token id the next step's embedding gather can use
+        if ((unsigned)bi >= (unsigned)vocab) bi = 0;
         if (lane == 0) { o[j] = bi; s.otok[r] = bi; }
     }
     __syncthreads();
@@ -171,8 +174,8 @@ __global__ __launch_bounds__(256) void argmax_accept_kernel(const float *__restr
     }
 }
 void launch_argmax_accept(const float *pval, const int *pidx, int n_part, const StepState &s, int n_seqs, int m,
-                          int max_k, const GenState *gen, hipStream_t st) {
-    hipLaunchKernelGGL(argmax_accept_kernel, dim3(n_seqs), dim3(256), 0, st, pval, pidx, n_part, s, m, max_k, gen);
+                          int max_k, int vocab, const GenState *gen, hipStream_t st) {
+    hipLaunchKernelGGL(argmax_accept_kernel, dim3(n_seqs), dim3(256), 0, st, pval, pidx, n_part, s, m, max_k, vocab, gen);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -253,8 +256,25 @@ void launch_trigger(const GenState *gen_dev, const StepState &s, int n_seqs, int
     hipLaunchKernelGGL(trigger_kernel, dim3(n_seqs), dim3(256), 0, st, gen_dev, s, max_k);
 }
 
+// check_offsets (callers whose document list lives in device memory, where the host cannot look):
+// the list must start at 0, never decrease and end at ref_len; otherwise result = (-1, -1, -1) and
+// nothing is scanned (the scan's backward walk relies on positions inside their documents).
 __global__ __launch_bounds__(256) void trigger_plain_kernel(const int *y, int y_len, const int *ref, const int *doc_offsets,
-                                                            const int *ref_doc, int ref_len, int n, int *result) {
+                                                            const int *ref_doc, int ref_len, int n_docs, int n, int *result,
+                                                            int check_offsets) {
+    if (ref_len <= 0 || n_docs <= 0) {
+        if (threadIdx.x == 0) { result[0] = 0; result[1] = -1; result[2] = -1; }
+        return;
+    }
+    if (check_offsets) {
+        int bad = 0;
+        for (int j = threadIdx.x; j < n_docs; j += blockDim.x) bad |= doc_offsets[j + 1] < doc_offsets[j];
+        if (threadIdx.x == 0) bad |= (doc_offsets[0] != 0) | (doc_offsets[n_docs] != ref_len);
+        if (__syncthreads_or(bad)) {
+            if (threadIdx.x == 0) { result[0] = -1; result[1] = -1; result[2] = -1; }
+            return;
+        }
+    }
     unsigned long long best = scan_reference(y, y_len, ref, doc_offsets, ref_doc, ref_len, n);
     if (threadIdx.x != 0) return;
     if (best == 0ull) { result[0] = 0; result[1] = -1; result[2] = -1; return; }
@@ -263,8 +283,9 @@ __global__ __launch_bounds__(256) void trigger_plain_kernel(const int *y, int y_
     result[0] = 1; result[1] = doc; result[2] = p - doc_offsets[doc];
 }
 void launch_trigger_plain(const int *y, int y_len, const int *ref, const int *doc_offsets, const int *ref_doc,
-                          int ref_len, int n, int *result, hipStream_t st) {
-    hipLaunchKernelGGL(trigger_plain_kernel, dim3(1), dim3(256), 0, st, y, y_len, ref, doc_offsets, ref_doc, ref_len, n, result);
+                          int ref_len, int n_docs, int n, int *result, bool check_offsets, hipStream_t st) {
+    hipLaunchKernelGGL(trigger_plain_kernel, dim3(1), dim3(256), 0, st, y, y_len, ref, doc_offsets, ref_doc, ref_len, n_docs, n,
+                       result, check_offsets ? 1 : 0);
 }
 
 // ref_doc[p] = the document that contains flat position p (doc_offsets non-decreasing)

@@ -8,6 +8,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <array>
 #include <map>
 #include <string>
 #include <utility>
@@ -18,6 +19,7 @@
 #include "kernels.h"
 
 static thread_local std::string g_err;      // errors of calls that have no context
+void llma_set_error_text(const char *text) { g_err = text ? text : ""; }   // for the library's other source files
 
 #define PREFILL_ROWS_F32 48      // fp32 path: prompt rows per pass
 #define PREFILL_ROWS_MAX 2048    // bf16 path: prompt rows per pass (whole prompt when it fits)
@@ -26,6 +28,8 @@ struct EventPair { hipEvent_t a, b; };
 
 enum StepKind { STEP_PREFILL = 0, STEP_VERIFY = 1, STEP_GEN = 2 };
 
+// what a captured step graph was recorded for: (kind, sequences, rows per sequence, attention chunks, slot)
+typedef std::array<int, 5> GraphKey;
 struct GraphSlot { int seen = 0; hipGraphExec_t exec = nullptr; };
 
 struct llma_ctx {
@@ -33,7 +37,7 @@ struct llma_ctx {
     hipStream_t st = nullptr;          // the caller's stream: everything is ordered on it
     hipStream_t run_st = nullptr;      // where the launchers enqueue: st, or cap_st while capturing
     hipStream_t cap_st = nullptr;      // private stream used only to capture step graphs
-    std::map<uint64_t, GraphSlot> graphs;
+    std::map<GraphKey, GraphSlot> graphs;
     int *pin_counts = nullptr;         // pinned host ints the decoding loop's output counts are copied into
     hipEvent_t cnt_ev[2] = {nullptr, nullptr};
     bool bf16 = false;
@@ -407,6 +411,8 @@ static int forward_bf16(llma_ctx *c, int n_seqs, int m, int n_chunks, bool lm_he
     // streamed once for all rows); the steps in its split-K form, because a few hundred rows alone make
     // too few workgroups to fill the chip.  Steps of up to 48 rows use the tile-K GEMM.
     const bool panel = !lm_head || R > 48;
+    bool refused = false;
+    auto tilek_gemm = [&](GemmArgs &ga) { refused = !launch_gemm_bf16(ga, st) || refused; };
     auto panel_gemm = [&](GemmArgs &ga) {
         if (lm_head && ga.plan.n_split > 1) { ga.ksplit = ga.plan.n_split; ga.part = c->part; }
         launch_gemm_panel_bf16(ga, st);
@@ -425,13 +431,13 @@ static int forward_bf16(llma_ctx *c, int n_seqs, int m, int n_chunks, bool lm_he
         ga.row_pos = c->s.row_pos; ga.row_slot = c->s.row_slot; ga.row_cs = c->s.row_cs; ga.q_hi = c->q; ga.q_lo = c->q_lo;
         ga.k_hi = c->kc[l]; ga.k_lo = c->kc_lo[l]; ga.v_hi = c->vc[l]; ga.v_lo = c->vc_lo[l];
         if (panel) { launch_rstd_rows(c->ssq, d / 16, g.rms_eps, c->rstd, R, st); panel_gemm(ga); }
-        else launch_gemm_bf16(ga, st);
+        else tilek_gemm(ga);
         aa.Khi = c->kc[l]; aa.Klo = c->kc_lo[l]; aa.Vhi = c->vc[l]; aa.Vlo = c->vc_lo[l];
         launch_attn_bf16(aa, st);
         ga = base;
         ga.W = c->wo[l]; ga.plan = c->plan_o; ga.Xhi = c->att_hi; ga.Xlo = c->att_lo; ga.epi = EPI_RESID; ga.out = c->h;
         ga.gain = c->n2[l]; ga.nx_hi = c->xhi; ga.nx_lo = c->xlo; ga.ssq_out = c->ssq;
-        if (panel) panel_gemm(ga); else launch_gemm_bf16(ga, st);
+        if (panel) panel_gemm(ga); else tilek_gemm(ga);
         ga = base;
         ga.W = c->wgu[l]; ga.plan = c->plan_gu; ga.Xhi = c->xhi; ga.Xlo = c->xlo; ga.epi = EPI_SWIGLU; ga.ssq_in = c->ssq;
         ga.act_hi = c->act_hi; ga.act_lo = c->act_lo; ga.act_KSp = c->plan_down.KSp;
@@ -443,24 +449,25 @@ static int forward_bf16(llma_ctx *c, int n_seqs, int m, int n_chunks, bool lm_he
             HIP_TRY(c, hipEventCreate(&ep.a));
             HIP_TRY(c, hipEventCreate(&ep.b));
             HIP_TRY(c, hipEventRecord(ep.a, st));
-            launch_gemm_bf16(ga, st);
+            tilek_gemm(ga);
             HIP_TRY(c, hipEventRecord(ep.b, st));
             c->events.push_back(ep);
         } else {
-            launch_gemm_bf16(ga, st);
+            tilek_gemm(ga);
         }
         ga = base;
         ga.W = c->wd[l]; ga.plan = c->plan_down; ga.Xhi = c->act_hi; ga.Xlo = c->act_lo; ga.epi = EPI_RESID; ga.out = c->h;
         ga.gain = (l + 1 < L) ? c->n1[l + 1] : c->final_norm; ga.nx_hi = c->xhi; ga.nx_lo = c->xlo; ga.ssq_out = c->ssq;
-        if (panel) panel_gemm(ga); else launch_gemm_bf16(ga, st);
+        if (panel) panel_gemm(ga); else tilek_gemm(ga);
     }
     if (lm_head) {
         GemmArgs ga = base;
         ga.W = c->lm_head; ga.plan = c->plan_lm; ga.Xhi = c->xhi; ga.Xlo = c->xlo; ga.epi = EPI_LMHEAD; ga.ssq_in = c->ssq;
         ga.out = c->logits_dump; ga.pval = c->pval; ga.pidx = c->pidx; ga.n_part = c->n_part;
         if (panel) { launch_rstd_rows(c->ssq, d / 16, g.rms_eps, c->rstd, R, st); panel_gemm(ga); }
-        else launch_gemm_bf16(ga, st);
+        else tilek_gemm(ga);
     }
+    if (refused) return fail(c, LLMA_E_INVAL, "forward: a step of %d rows reached the decoding-step GEMM (1..48 rows)", R);
     HIP_TRY(c, hipGetLastError());
     return LLMA_OK;
 }
@@ -489,7 +496,7 @@ static int step_body(llma_ctx *c, int kind, int n_seqs, int m, int n_chunks, int
     launch_setup_step_rows(c->s, n_seqs, m, mk, c->cs_table, c->cfg.head_dim / 2, st);
     int rc = forward(c, n_seqs, m, n_chunks, true, slot);
     if (rc) return rc;
-    launch_argmax_accept(c->pval, c->pidx, c->n_part, c->s, n_seqs, m, mk, kind == STEP_GEN ? c->gen_dev : nullptr, st);
+    launch_argmax_accept(c->pval, c->pidx, c->n_part, c->s, n_seqs, m, mk, c->cfg.vocab, kind == STEP_GEN ? c->gen_dev : nullptr, st);
     return LLMA_OK;
 }
 
@@ -510,7 +517,7 @@ static int run_step(llma_ctx *c, int kind, int n_seqs, int m, int t_max, int slo
     if (c->bf16 && n_chunks > c->nc_max) n_chunks = c->nc_max;
     c->run_st = c->st;
     if (!c->opt_graph || c->opt_timing || c->graphs.size() > 256) return step_body(c, kind, n_seqs, m, n_chunks, slot);
-    const uint64_t key = ((uint64_t)kind << 60) | ((uint64_t)n_seqs << 48) | ((uint64_t)m << 40) | ((uint64_t)n_chunks << 20) | (uint64_t)slot;
+    const GraphKey key = {kind, n_seqs, m, n_chunks, slot};     // every field that shapes a launch or is baked into one
     GraphSlot &gs = c->graphs[key];
     if (gs.exec == nullptr) {
         if (gs.seen++ == 0) return step_body(c, kind, n_seqs, m, n_chunks, slot);   // first time eagerly
@@ -671,18 +678,21 @@ extern "C" int llma_find_trigger(const int32_t *y, int32_t y_len, const int32_t 
     const int ref_len = n_docs > 0 ? doc_offsets[n_docs] : 0;
     if (ref_len > 0 && !ref) return fail(nullptr, LLMA_E_INVAL, "llma_find_trigger: null reference");
     if (ref_len == 0 || y_len < n) return 0;
+    // device scratch for this call: [y | ref | doc_offsets | result(4)] copied in at once, then ref_doc
+    const size_t n_in = (size_t)y_len + (size_t)ref_len + (size_t)(n_docs + 1) + 4;
+    std::vector<int> stage(n_in);
+    memcpy(stage.data(), y, (size_t)y_len * 4);
+    memcpy(stage.data() + y_len, ref, (size_t)ref_len * 4);
+    memcpy(stage.data() + y_len + ref_len, doc_offsets, (size_t)(n_docs + 1) * 4);
     int *buf = nullptr;
-    const size_t ints = (size_t)y_len + 2 * (size_t)ref_len + (n_docs + 1) + 4;
-    hipError_t e = hipMalloc((void **)&buf, ints * 4);
+    hipError_t e = hipMalloc((void **)&buf, (n_in + (size_t)ref_len) * 4);
     if (e != hipSuccess) return fail(nullptr, LLMA_E_NOMEM, "llma_find_trigger: hipMalloc: %s", hipGetErrorString(e));
-    int *dy = buf, *dref = dy + y_len, *ddoc = dref + ref_len, *doff = ddoc + ref_len, *dres = doff + n_docs + 1;
+    int *dy = buf, *dref = dy + y_len, *doff = dref + ref_len, *dres = doff + n_docs + 1, *ddoc = dres + 4;
     int res[3] = {0, -1, -1};
-    e = hipMemcpy(dy, y, (size_t)y_len * 4, hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(dref, ref, (size_t)ref_len * 4, hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemcpy(doff, doc_offsets, (size_t)(n_docs + 1) * 4, hipMemcpyHostToDevice);
+    e = hipMemcpy(buf, stage.data(), n_in * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) {
         launch_fill_ref_doc(doff, n_docs, ddoc, ref_len, nullptr);
-        launch_trigger_plain(dy, y_len, dref, doff, ddoc, ref_len, n, dres, nullptr);
+        launch_trigger_plain(dy, y_len, dref, doff, ddoc, ref_len, n_docs, n, dres, false, nullptr);
         e = hipGetLastError();
     }
     if (e == hipSuccess) e = hipMemcpy(res, dres, 12, hipMemcpyDeviceToHost);
@@ -736,6 +746,11 @@ extern "C" int llma_verify_step_batch(llma_ctx *c, int32_t n_seqs, const int32_t
     HIP_TRY(c, hipMemcpyAsync(em.data(), c->s.emit, (size_t)n_seqs * (mk + 1) * 4, hipMemcpyDeviceToHost, st));
     HIP_TRY(c, hipStreamSynchronize(st));
     HIP_TRY(c, hipGetLastError());
+    for (int b = 0; b < n_seqs; ++b) {
+        bool ok = nacc[b] >= 0 && nacc[b] <= k && nxt[b] >= 0 && nxt[b] < g.vocab;
+        for (int j = 0; ok && j <= nacc[b]; ++j) ok = em[(size_t)b * (mk + 1) + j] >= 0 && em[(size_t)b * (mk + 1) + j] < g.vocab;
+        if (!ok) return fail(c, LLMA_E_HIP, "llma_verify_step: device returned accepted count %d / token %d outside their ranges for slot %d", nacc[b], nxt[b], seqs[b]);
+    }
     for (int b = 0; b < n_seqs; ++b) {
         c->T_host[seqs[b]] += nacc[b] + 1;
         c->pending_host[seqs[b]] = nxt[b];
@@ -951,7 +966,7 @@ extern "C" int llma_time_ffn_gemm(llma_ctx *c, int32_t rows, int32_t reps, doubl
         HIP_TRY(c, hipEventRecord(e0, c->st));
         for (int r = 0; r < n; ++r) {
             ga.W = c->wgu[r % g.n_layers];
-            launch_gemm_bf16(ga, c->st);
+            if (!launch_gemm_bf16(ga, c->st)) return fail(c, LLMA_E_RANGE, "llma_time_ffn_gemm: rows %d outside 1..48", rows);
         }
         HIP_TRY(c, hipEventRecord(e1, c->st));
         HIP_TRY(c, hipEventSynchronize(e1));

@@ -2,7 +2,7 @@
 
 Bars:
   - trigger positions, accepted counts, step traces, token ids: bit-exact;
-  - logits: |gpu - oracle| <= 1e-2 + 2e-2*|oracle| for bf16 models, <= 1e-4 + 1e-4*|oracle| for
+  - logits: |gpu - oracle| <= 1e-2 + 2e-2*|oracle| for bf16 models, <= 1e-4 (absolute) for
     fp32 models (oracle in float64);
   - emitted tokens identical to the oracle's except where the oracle's top-2 logit gap is
     below that tolerance; every such near-tie is printed.
@@ -17,7 +17,7 @@ from oracle import (OracleModel, CachedLLM, greedy_decode, llma_decode, match_ng
 pytestmark = pytest.mark.gpu
 
 BF16_ATOL, BF16_RTOL = 1e-2, 2e-2
-F32_ATOL, F32_RTOL = 1e-4, 1e-4
+F32_ATOL, F32_RTOL = 1e-4, 0.0
 
 
 def tol(cfg):
@@ -421,4 +421,43 @@ def test_argument_errors_leave_context_unchanged(llma):
         ctx.reset(5)
     na, nxt, em = ctx.verify_step([])                           # still usable
     assert na == 0 and len(em) == 1
+    ctx.close()
+
+
+def test_step_graphs_of_prompt_passes_with_256_rows_apart(llma):
+    """Captured step graphs are looked up by (kind, sequences, rows, attention chunks, slot).  Two prompt
+    passes whose row counts differ by 256 -- 100 rows on top of 256 cached positions and 356 rows on an
+    empty cache, both three attention chunks -- must not share a graph: every round of the sequence
+    below (the second captures, the third replays) gives the state and logits of the eager path."""
+    cfg = MINI64
+    w = synth.make_weights(cfg, 91, gain_jitter=0.2)
+    p257 = synth.uniform_tokens(9, 1, 257, cfg.vocab)
+    q101 = synth.uniform_tokens(9, 2, 101, cfg.vocab)
+    r357 = synth.uniform_tokens(9, 3, 357, cfg.vocab)
+    draft = synth.uniform_tokens(9, 4, 4, cfg.vocab).tolist()
+
+    def run(ctx, rounds):
+        out = []
+        ctx.enable_logits_dump(5)
+        for _ in range(rounds):
+            ctx.reset(); ctx.prefill(p257); ctx.prefill(q101)
+            st = ctx.get_state()
+            ctx.verify_step(draft)
+            out.append((st, ctx.get_state(), ctx.logits(5).copy()))
+            ctx.reset(); ctx.prefill(r357)
+            st = ctx.get_state()
+            ctx.verify_step(draft)
+            out.append((st, ctx.get_state(), ctx.logits(5).copy()))
+        return out
+
+    eager = llma.Context(cfg, w, max_seq=600, max_batch=1, max_k=8)
+    eager.set_option(llma.LLMA_OPT_USE_GRAPH, 0)
+    want = run(eager, 1)
+    eager.close()
+    assert want[0][0] == (356, int(q101[-1])) and want[1][0] == (356, int(r357[-1]))
+    ctx = llma.Context(cfg, w, max_seq=600, max_batch=1, max_k=8)
+    got = run(ctx, 4)
+    for i, (st0, st1, lg) in enumerate(got):
+        assert st0 == want[i % 2][0] and st1 == want[i % 2][1], (i, st0, st1)
+        assert np.array_equal(lg, want[i % 2][2]), f"round {i // 2}, case {i % 2}: logits differ from the eager path"
     ctx.close()
