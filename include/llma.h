@@ -123,6 +123,27 @@ int llma_find_trigger(const int32_t *y, int32_t y_len,
                       const int32_t *ref, const int32_t *doc_offsets, int32_t n_docs,
                       int32_t n, int32_t *doc_out, int32_t *pos_out);
 
+/* The same scan for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  It calls no hipMalloc / hipFree / other
+ * allocating routine and copies nothing between host and device: inputs and the result are
+ * DEVICE memory of the caller, the work is enqueued on hip_stream (a hipStream_t, NULL = default
+ * stream) and the call returns without synchronising.
+ *   y_dev int32[y_len], ref_dev int32[ref_len], doc_offsets_dev int32[n_docs+1] as above;
+ *   result_dev int32[3] receives (matched, doc, pos): (1, doc, pos), (0, -1, -1) when nothing
+ *   matches, or (LLMA_E_INVAL, -1, -1) when the kernel finds that doc_offsets does not start at 0,
+ *   decreases somewhere or does not end at ref_len (the host cannot read device memory to check).
+ * The one buffer the scan needs beyond inputs and outputs (the document index of every reference
+ * position) is a static device array of LLMA_TRIGGER_STATIC_MAX_REF ints (4 MiB) that every GPU
+ * the library runs on holds until the process ends; ref_len beyond it returns LLMA_E_RANGE (use
+ * llma_find_trigger).  All calls on one GPU share that array: calls that overlap in time on
+ * the same GPU (different streams or threads) race and must be serialised by the caller; calls
+ * one after the other on a stream are fine (every entry a call reads it has written first).
+ * Returns LLMA_OK once the work is enqueued; INVAL (null pointer, negative count, n < 1), RANGE, HIP. */
+#define LLMA_TRIGGER_STATIC_MAX_REF (1 << 20)
+int llma_find_trigger_static(const int32_t *y_dev, int32_t y_len, const int32_t *ref_dev, int32_t ref_len,
+                             const int32_t *doc_offsets_dev, int32_t n_docs, int32_t n,
+                             int32_t *result_dev, void *hip_stream);
+
 /* One verification step (paper: Eq. 3 and the draft-comparison loop of Algorithm 1) for slot `seq`.
  * draft: HOST int32[k], the copied tokens d_pos..d_pos+k-1; 0 <= k <= max_k; k = 0 is a
  * plain greedy step (Eq. 2).  The rows [pending, draft[0..k)] go through the model at

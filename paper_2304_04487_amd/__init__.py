@@ -24,8 +24,9 @@ EXPORTS = [
     "llma_create", "llma_destroy", "llma_last_error", "llma_reset", "llma_prefill", "llma_get_state",
     "llma_set_pending", "llma_kv_import", "llma_find_trigger", "llma_verify_step",
     "llma_verify_step_batch", "llma_generate", "llma_generate_batch", "llma_set_logits_dump", "llma_set_option",
-    "llma_get_kernel_timing", "llma_time_ffn_gemm", "llma_device_bytes",
+    "llma_get_kernel_timing", "llma_time_ffn_gemm", "llma_device_bytes", "llma_find_trigger_static",
 ]
+LLMA_TRIGGER_STATIC_MAX_REF = 1 << 20
 
 
 class LlmaError(RuntimeError):
@@ -73,6 +74,7 @@ def load_library() -> ctypes.CDLL:
     lib.llma_set_pending.argtypes = [vp, c_int32, c_int32]
     lib.llma_kv_import.argtypes = [vp, c_int32, c_int32, vp, vp, c_int32]
     lib.llma_find_trigger.argtypes = [i32p, c_int32, i32p, i32p, c_int32, c_int32, i32p, i32p]
+    lib.llma_find_trigger_static.argtypes = [vp, c_int32, vp, c_int32, vp, c_int32, c_int32, vp, vp]
     lib.llma_verify_step.argtypes = [vp, c_int32, i32p, c_int32, i32p, i32p, i32p]
     lib.llma_verify_step_batch.argtypes = [vp, c_int32, i32p, i32p, c_int32, i32p, i32p, i32p]
     lib.llma_generate.argtypes = [vp, c_int32, i32p, c_int32, i32p, i32p, c_int32, c_int32, c_int32, c_int32,
@@ -110,6 +112,18 @@ def llma_find_trigger(y, ref, doc_offsets, n: int):
     doc, pos = c_int32(-1), c_int32(-1)
     rc = _check(lib.llma_find_trigger(_ptr(y), len(y), _ptr(ref), _ptr(offs), len(offs) - 1, n, byref(doc), byref(pos)))
     return bool(rc), doc.value, pos.value
+
+
+def llma_find_trigger_static(y_dev, ref_dev, doc_offsets_dev, n: int, result_dev, stream=None):
+    """The allocation-free trigger scan on DEVICE int32 tensors (anything with data_ptr() and
+    numel()); result_dev: 3 device ints (matched, doc, pos).  Enqueues on `stream` (an object with
+    .cuda_stream, or None for the default stream) and returns without synchronising."""
+    lib = load_library()
+    n_docs = max(int(doc_offsets_dev.numel()) - 1, 0)
+    st = c_void_p(stream.cuda_stream) if stream is not None else None
+    _check(lib.llma_find_trigger_static(c_void_p(y_dev.data_ptr()), int(y_dev.numel()), c_void_p(ref_dev.data_ptr()),
+                                        int(ref_dev.numel()), c_void_p(doc_offsets_dev.data_ptr()), n_docs, n,
+                                        c_void_p(result_dev.data_ptr()), st))
 
 
 class Context:

@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libllma.so")
-SOURCES = ["kernels_bf16.hip", "kernels_f32.hip", "kernels_misc.hip", "llma_api.hip"]
+SOURCES = ["kernels_bf16.hip", "kernels_f32.hip", "kernels_misc.hip", "llma_api.hip", "llma_noalloc.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wno-unused-result",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
