@@ -36,18 +36,29 @@ def _widen(a: np.ndarray, dtype) -> np.ndarray:
 
 class _LayersWidenedOnDemand:
     """The per-layer weight dicts of a model whose matrices stay in their storage format;
-    iterating yields one layer at a time, widened to the arithmetic dtype (and dropped
-    again when the next one is asked for)."""
+    iterating yields one layer at a time, widened to the arithmetic dtype.  The widened
+    matrices of consecutive layers share one set of buffers (same shapes), so a yielded
+    layer is only valid until the next one is asked for -- which is how forward() uses it."""
 
     def __init__(self, raw_layers, dtype):
         self.raw, self.dtype = raw_layers, dtype
+        self.buf = {}
 
     def __len__(self):
         return len(self.raw)
 
+    def _widen_into_buffer(self, name, a):
+        if a.dtype != np.uint16 or self.dtype != np.float32:
+            return _widen(a, self.dtype)
+        b = self.buf.get(name)
+        if b is None or b.shape != a.shape:
+            b = self.buf[name] = np.empty(a.shape, dtype=np.float32)
+        np.left_shift(a, 16, out=b.view(np.uint32), dtype=np.uint32, casting="unsafe")   # same exact widening as _widen
+        return b
+
     def __iter__(self):
         for lw in self.raw:
-            yield {k: (_widen(v, self.dtype) if v.ndim == 2 else v.astype(self.dtype)) for k, v in lw.items()}
+            yield {k: (self._widen_into_buffer(k, v) if v.ndim == 2 else v.astype(self.dtype)) for k, v in lw.items()}
 
 
 def rmsnorm(x: np.ndarray, g: np.ndarray, eps: float) -> np.ndarray:
@@ -92,7 +103,8 @@ class OracleModel:
         if lazy:
             self.layers = _LayersWidenedOnDemand(weights["layers"], dtype)
         else:
-            self.layers = list(_LayersWidenedOnDemand(weights["layers"], dtype))
+            self.layers = [{k: (_widen(v, dtype) if v.ndim == 2 else v.astype(dtype)) for k, v in lw.items()}
+                           for lw in weights["layers"]]
 
     def new_cache(self, capacity: int) -> KVCache:
         c = self.cfg
