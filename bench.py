@@ -12,6 +12,10 @@ Prints ONE JSON line.  Besides the driver's fields it carries
   roofline     -- the FFN gate/up GEMM (largest share of bytes per step) against peak HBM bandwidth,
   cpu_baseline -- the CPU oracle timed on this host on a bounded sample of the same workload,
   extras       -- decode-only rate, the k = 0 / k = 1 rates of the same library, step statistics.
+
+Other modes (not the default line): --microbench = the isolated verification-step sweep (16 sequences x
+4096-position caches, k in {1..32}, all-accept / all-reject drafts, both row conventions), --grid = the
+(n, k) grid of the paper's hyper-parameter figures, --profile-steps = a few steps for rocprofv3.
 """
 from __future__ import annotations
 
@@ -47,56 +51,195 @@ def measured_traffic():
     return None
 
 
-def cpu_baseline(wl, prompt_len: int, budget_s: float = 25.0):
-    """The oracle as it stands, on a bounded sample: a model with the first 4 of the L layers plus
-    the LM head (float32 copies of the weights), one-row greedy steps on top of a T = prompt_len
-    cache filled by feeding uniform tokens, per-layer and head time separated and extrapolated
-    linearly to L layers.  Only this function (and the tests) touch oracle/."""
-    import synth
-    from oracle import OracleModel
-    cfg = wl.model
-    nl = 4
-    w = synth.make_weights(cfg, wl.seed, n_layers=nl)
-    om = OracleModel(cfg, w, dtype=np.float32)
-    del w
-    T = prompt_len
-    cache = om.new_cache(T + 640)
-    for l in range(nl):                      # KV fill stands in for the prompt's keys/values
-        cache.k[l][:, :T] = 1.0
-        cache.v[l][:, :T] = 0.5
-    tok = 1
-    t_full, n_full = 0.0, 0
-    t0 = time.perf_counter()
-    while True:
-        s = time.perf_counter()
-        lg = om.forward([tok], cache, T + n_full)
-        tok = int(np.argmax(lg[0]))
-        t_full += time.perf_counter() - s
-        n_full += 1
-        if n_full >= 3 and (time.perf_counter() - t0 > budget_s / 2 or n_full >= 600):
-            break
-    # head alone: a 0-layer model
-    om.layers = []
-    t_head, n_head = 0.0, 0
-    while n_head < 3 or (t_head < budget_s / 6 and n_head < 600):
-        s = time.perf_counter()
-        om.forward([tok], cache, T)
-        t_head += time.perf_counter() - s
-        n_head += 1
-    per_tok_full, per_tok_head = t_full / n_full, t_head / n_head
-    per_layer = max(per_tok_full - per_tok_head, 0.0) / nl
-    per_tok = per_tok_head + cfg.n_layers * per_layer
+def _host_threads():
     try:
         import threadpoolctl
-        cores = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] or [1])
+        return int(max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] or [1]))
     except Exception:
-        cores = os.cpu_count() or 1
+        return int(os.cpu_count() or 1)
+
+
+def _cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(wl, y_target, ref, offs, k: int, n_tokens: int = 64):
+    """The oracle as it stands, timed on this host at FULL depth on a bounded sample of the workload:
+    the first `n_tokens` output tokens, decoded twice by the oracle's own loops -- stepwise greedy
+    (Eq. 2) and LLMA (Algorithm 1) with the benchmark's reference.  Every step runs the oracle's real
+    forward (all layers, float32 copies of the weights, 1 or 1 + k_eff rows on top of a cache of prompt
+    length); which tokens a step emits is taken from the known target output, the paper's own
+    target-guided way of timing a decoding sequence, so both loops walk exactly the step sequence of
+    the real run.  The prompt pass is not timed and not computed on the CPU (minutes): the cache
+    below the prompt length holds N(0,1) filler, which costs the same to attend over.
+    Falls back to a 4-layer extrapolation (labelled) if the float32 weights do not fit the host.
+    Only this function (and the tests) touch oracle/."""
+    import synth
+    from oracle import OracleModel, ScriptedLLM, greedy_decode, llma_decode, docs_from_flat
+    cfg = wl.model
+    T0 = wl.prompt_len - 1
+    target = [int(t) for t in y_target[:n_tokens]]
+    extrapolated = False
+    try:
+        w = synth.make_weights(cfg, wl.seed)
+        om = OracleModel(cfg, w, dtype=np.float32)
+        n_layers = cfg.n_layers
+    except MemoryError:
+        w = synth.make_weights(cfg, wl.seed, n_layers=4)
+        om = OracleModel(cfg, w, dtype=np.float32)
+        n_layers, extrapolated = 4, True
+    del w
+
+    class TimedTargetLLM:
+        """llm(y, drafts): the oracle's forward over [last token] + drafts (timed), outputs from the target."""
+
+        def __init__(self):
+            self.cache = om.new_cache(T0 + n_tokens + k + 8)
+            filler = synth.normal_f32(wl.seed, 77, 1.0, (cfg.n_heads, T0, cfg.head_dim))
+            for l in range(n_layers):
+                self.cache.k[l][:, :T0] = filler
+                self.cache.v[l][:, :T0] = filler
+            self.script = ScriptedLLM(target)
+            self.seconds, self.calls, self.rows = 0.0, 0, 0
+
+        def __call__(self, y, drafts):
+            rows = [int(y[-1]) if len(y) else 1] + [int(t) for t in drafts]
+            t = time.perf_counter()
+            om.forward(rows, self.cache, T0 + len(y))
+            self.seconds += time.perf_counter() - t
+            self.calls += 1
+            self.rows += len(rows)
+            return self.script(y, drafts)
+
+    D = docs_from_flat(ref, offs)
+    g = TimedTargetLLM()
+    g(target[:0], [])                                   # warm-up call (first-touch of the cache pages, BLAS threads)
+    g.seconds, g.calls, g.rows = 0.0, 0, 0
+    yg = greedy_decode(g, n_tokens)
+    l = TimedTargetLLM()
+    yl, trace = llma_decode(l, D, wl.n, k, n_tokens)
+    assert yg == target and yl == target
+    scale = cfg.n_layers / n_layers if extrapolated else 1.0
+    greedy_rate = n_tokens / (g.seconds * scale)
+    llma_rate = n_tokens / (l.seconds * scale)
     return {
-        "value": round(1.0 / per_tok, 4), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-        "sample": f"numpy float32 oracle, {nl} of {cfg.n_layers} layers + LM head, {n_full} one-row greedy steps over a "
-                  f"{T}-position KV cache; per-layer time ({per_layer * 1e3:.1f} ms) x {cfg.n_layers} + head "
-                  f"({per_tok_head * 1e3:.1f} ms), decode only (no prompt processing)",
+        "value": round(llma_rate, 4), "unit": "tokens/s", "cores": _host_threads(), "kind": "oracle",
+        "cpu_model": _cpu_model(),
+        "greedy_tokens_per_s": round(greedy_rate, 4), "llma_tokens_per_s": round(llma_rate, 4),
+        "llma_steps": len(trace), "greedy_steps": g.calls,
+        "sample": (f"numpy float32 oracle at full depth ({cfg.n_layers} layers), first {n_tokens} of {wl.max_new} output tokens, decode only: "
+                   f"greedy loop {g.calls} one-row forwards in {g.seconds:.1f} s, LLMA loop (n={wl.n}, k={k}, the benchmark's reference) "
+                   f"{l.calls} forwards / {l.rows} rows in {l.seconds:.1f} s; emitted tokens follow the known output (target-guided), "
+                   f"cache below the prompt length holds N(0,1) filler instead of a CPU prompt pass; value = the LLMA loop"
+                   + ("; EXTRAPOLATED from 4 layers (float32 weights did not fit the host)" if extrapolated else "")),
     }
+
+
+def microbench(args, torch, synth, llma):
+    """The isolated verification-step microbenchmark: LLaMA-7B shape, 16 sequences, each on a KV cache of
+    4096 positions, one verification step for all of them, k in {1, 2, 4, 8, 16, 32}.  Both readings of
+    "k" are timed: m = k + 1 rows per sequence (the paper's: pending token + k copies) and m = k rows.
+    Drafts are forced to all-reject (first copy differs from the model's own token) and to all-accept
+    (copies = the model's own continuation, found by repeating the step from the restored cache until
+    every copy is accepted).  Every timed step starts from the same cache length (llma_truncate), is
+    bracketed by an event pair on the library's stream, 5 warm-ups then `--mb-iters` timed steps.
+    Caches: "imported" = N(0,1) values rounded to bf16 and imported (their lo planes are zero and are
+    not read); "computed" = the library's own prompt pass over 4096 random tokens (hi + lo planes, what
+    a real batched generation holds) for k in {1, 8, 32}."""
+    cfg = synth.LLAMA_7B
+    B, T, seed = 16, 4096, 4242
+    ks = [int(x) for x in args.mb_k.split(",")]
+    iters, warm = args.mb_iters, 5
+    w = synth.make_weights(cfg, seed)
+    ctx = llma.Context(cfg, w, max_seq=T + 64, max_batch=B, max_k=32, kv_split=True)
+    del w
+    slots = list(range(B))
+    pend = [100 + b for b in slots]
+    wbytes = 2 * cfg.streamed_params
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def restore():
+        for b in slots:
+            ctx.truncate(T, b)
+            ctx.set_pending(pend[b], b)
+
+    def sweep(cache_kind, k_list, modes):
+        rows_out = []
+        for k in k_list:
+            for conv, kd in (("m=k+1", k), ("m=k", k - 1)):
+                for mode in modes:
+                    if kd == 0 and mode == "accept":
+                        continue                                   # no copies: one case only
+                    drafts = synth.uniform_tokens(seed, 50 + 7 * k + (conv == "m=k"), B * max(kd, 1), cfg.vocab).reshape(B, max(kd, 1))[:, :kd].copy()
+                    want = kd if mode == "accept" else 0
+                    for _ in range(kd + 2):                        # force the drafts
+                        restore()
+                        na, nxt, em = ctx.verify_step_batch(slots, drafts)
+                        if kd == 0 or all(int(a) == want for a in na):
+                            break
+                        for b in slots:
+                            if mode == "accept" and na[b] < kd:
+                                drafts[b, na[b]] = nxt[b]          # the model's own token at the first rejected position
+                            elif mode == "reject" and na[b] > 0:
+                                drafts[b, 0] = (em[b][0] + 1) % cfg.vocab
+                    for _ in range(warm):
+                        restore()
+                        ctx.verify_step_batch(slots, drafts)
+                    times = []
+                    for _ in range(iters):
+                        restore()
+                        torch.cuda.synchronize()
+                        ev0.record()
+                        na, nxt, em = ctx.verify_step_batch(slots, drafts)
+                        ev1.record()
+                        torch.cuda.synchronize()
+                        times.append(ev0.elapsed_time(ev1))
+                        assert kd == 0 or all(int(a) == want for a in na), (k, conv, mode, na)
+                    ms = float(np.mean(times))
+                    m = kd + 1
+                    rows = B * m
+                    kv_read = B * 2 * 2 * cfg.n_layers * cfg.d_model * (T + m)       # one bf16 plane: the algorithmic bytes
+                    kv_write = rows * 2 * 2 * cfg.n_layers * cfg.d_model
+                    alg = wbytes + kv_read + kv_write
+                    flops = 2.0 * rows * cfg.streamed_params + 4.0 * rows * (T + m) * cfg.d_model * cfg.n_layers
+                    r = {"cache": cache_kind, "k": k, "rows_per_seq": m, "convention": conv, "drafts": mode if kd else "none",
+                         "step_ms": round(ms, 3), "min_ms": round(float(np.min(times)), 3), "alg_GB": round(alg / 1e9, 2),
+                         "GBps": round(alg / ms / 1e6, 1), "hbm_frac": round(alg / ms / 1e6 / HBM_PEAK_GBS, 4),
+                         "useful_TFLOPs": round(flops / ms / 1e9, 1), "mfma_frac_of_dense_bf16_peak": round(flops / ms / 1e9 / 2500.0, 4)}
+                    rows_out.append(r)
+                    log(f"[mb] {cache_kind:9s} k={k:2d} {conv:5s} {r['drafts']:6s} rows {rows:4d}: {ms:8.3f} ms  {r['GBps']:7.1f} GB/s  "
+                        f"{r['hbm_frac']:.3f} of peak  {r['useful_TFLOPs']:7.1f} TFLOP/s useful")
+        return rows_out
+
+    table = []
+    if not args.mb_skip_imported:
+        t0 = time.time()
+        for b in slots:
+            for l in range(cfg.n_layers):
+                kk, vv = synth.make_kv_fill(cfg, seed + b, 1, T, l)
+                ctx.kv_import(b, l, torch.from_numpy(kk[0]).cuda(), torch.from_numpy(vv[0]).cuda(), T)
+        torch.cuda.synchronize()
+        log(f"[mb] imported {B} x {T}-position caches in {time.time() - t0:.0f}s")
+        table += sweep("imported", ks, ("reject", "accept"))
+    if not args.mb_skip_computed:
+        t0 = time.time()
+        for b in slots:
+            ctx.reset(b)
+            ctx.prefill(synth.uniform_tokens(seed, 900 + b, T + 1, cfg.vocab), b)
+            pend[b] = ctx.get_state(b)[1]
+        torch.cuda.synchronize()
+        log(f"[mb] computed {B} x {T}-position caches (prompt passes) in {time.time() - t0:.1f}s")
+        table += sweep("computed", [k for k in ks if k in (1, 8, 32)], ("reject",))
+    ctx.close()
+    print(json.dumps({"workload": "configs[4] verify-step microbenchmark: LLaMA-7B shape, 16 sequences x 4096-position KV caches",
+                      "iters": iters, "warmup": warm, "timer": "HIP event pair on the library's stream around llma_verify_step_batch",
+                      "peak_GBps": HBM_PEAK_GBS, "table": table}), flush=True)
 
 
 def main():
@@ -111,6 +254,12 @@ def main():
     ap.add_argument("--grid", action="store_true",
                     help="instead of the benchmark line: decode-only tokens/s and steps of the workload over the "
                          "paper's (n, k) grid, n in {1,2,3} x k in {4,8,12,16,18}, as a table and one JSON line")
+    ap.add_argument("--microbench", action="store_true",
+                    help="instead of the benchmark line: the isolated verification-step sweep (16 sequences x 4096 positions)")
+    ap.add_argument("--mb-k", default="1,2,4,8,16,32", help="microbenchmark: copy lengths")
+    ap.add_argument("--mb-iters", type=int, default=20, help="microbenchmark: timed steps per case")
+    ap.add_argument("--mb-skip-imported", action="store_true")
+    ap.add_argument("--mb-skip-computed", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=0,
                     help="profiling aid (for rocprofv3): skip the benchmark, run this many k-draft verification steps "
                          "on a random KV cache of prompt length plus one plain 256 MiB device copy, print nothing")
@@ -126,6 +275,9 @@ def main():
     if not torch.cuda.is_available():
         log("bench.py: no GPU visible")
         sys.exit(2)
+    if args.microbench:
+        microbench(args, torch, synth, llma)
+        return
     wl = synth.WORKLOADS[args.workload]
     cfg = wl.model
     k = wl.k if args.k is None else args.k
@@ -290,7 +442,7 @@ def main():
     }
     if not args.no_cpu_baseline:
         t0 = time.time()
-        out["cpu_baseline"] = cpu_baseline(wl, wl.prompt_len)
+        out["cpu_baseline"] = cpu_baseline(wl, y0, ref, offs, k)
         # the paper's model-free prediction of the step sequence from the known output (its
         # target-guided simulation), beside the realised one: also oracle code, so it lives here
         from oracle.decode import infer_decoding_sequence, docs_from_flat

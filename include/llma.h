@@ -97,6 +97,12 @@ int llma_reset(llma_ctx *ctx, int32_t seq);
 int llma_prefill(llma_ctx *ctx, int32_t seq, const int32_t *prompt, int32_t len);
 /* Reads the slot's state into HOST ints (either pointer may be NULL). pending = -1 if none. */
 int llma_get_state(llma_ctx *ctx, int32_t seq, int32_t *T, int32_t *pending);
+/* KV truncate on request (the operation every step ends with, paper: the rows of rejected copies
+ * are dropped): keeps the first new_len positions of slot `seq`, 0 <= new_len <= T, and leaves
+ * the pending token as it is.  The dropped rows stay in memory and are overwritten by later
+ * steps.  Used by the verify-step microbenchmark to return to the same cache length before every
+ * timed step.  Errors: RANGE (new_len outside [0, T]). */
+int llma_truncate(llma_ctx *ctx, int32_t seq, int32_t new_len);
 /* Sets the pending token of a slot (HOST value), e.g. after llma_kv_import. */
 int llma_set_pending(llma_ctx *ctx, int32_t seq, int32_t token);
 /* Replaces layer `layer` of slot `seq`'s KV cache by caller data and sets T = len once the

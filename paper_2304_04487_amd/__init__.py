@@ -24,7 +24,7 @@ EXPORTS = [
     "llma_create", "llma_destroy", "llma_last_error", "llma_reset", "llma_prefill", "llma_get_state",
     "llma_set_pending", "llma_kv_import", "llma_find_trigger", "llma_verify_step",
     "llma_verify_step_batch", "llma_generate", "llma_generate_batch", "llma_set_logits_dump", "llma_set_option",
-    "llma_get_kernel_timing", "llma_time_ffn_gemm", "llma_device_bytes", "llma_find_trigger_static",
+    "llma_get_kernel_timing", "llma_time_ffn_gemm", "llma_device_bytes", "llma_find_trigger_static", "llma_truncate",
 ]
 LLMA_TRIGGER_STATIC_MAX_REF = 1 << 20
 
@@ -72,6 +72,7 @@ def load_library() -> ctypes.CDLL:
     lib.llma_prefill.argtypes = [vp, c_int32, i32p, c_int32]
     lib.llma_get_state.argtypes = [vp, c_int32, i32p, i32p]
     lib.llma_set_pending.argtypes = [vp, c_int32, c_int32]
+    lib.llma_truncate.argtypes = [vp, c_int32, c_int32]
     lib.llma_kv_import.argtypes = [vp, c_int32, c_int32, vp, vp, c_int32]
     lib.llma_find_trigger.argtypes = [i32p, c_int32, i32p, i32p, c_int32, c_int32, i32p, i32p]
     lib.llma_find_trigger_static.argtypes = [vp, c_int32, vp, c_int32, vp, c_int32, c_int32, vp, vp]
@@ -189,6 +190,9 @@ class Context:
         t, p = c_int32(), c_int32()
         self._ck(self.lib.llma_get_state(self._h, seq, byref(t), byref(p)))
         return t.value, p.value
+
+    def truncate(self, new_len: int, seq: int = 0):
+        self._ck(self.lib.llma_truncate(self._h, seq, int(new_len)))
 
     def set_pending(self, token: int, seq: int = 0):
         self._ck(self.lib.llma_set_pending(self._h, seq, int(token)))

@@ -579,6 +579,16 @@ extern "C" int llma_get_state(llma_ctx *c, int32_t seq, int32_t *T, int32_t *pen
     return LLMA_OK;
 }
 
+extern "C" int llma_truncate(llma_ctx *c, int32_t seq, int32_t new_len) {
+    int rc = check_slot(c, seq, "llma_truncate");
+    if (rc) return rc;
+    if (new_len < 0 || new_len > c->T_host[seq])
+        return fail(c, LLMA_E_RANGE, "llma_truncate: new length %d outside [0, T = %d]", new_len, c->T_host[seq]);
+    c->T_host[seq] = new_len;
+    if (c->lo_from_host[seq] > new_len) c->lo_from_host[seq] = new_len;    // rows written from here on have lo planes
+    return push_state(c, seq);
+}
+
 extern "C" int llma_set_pending(llma_ctx *c, int32_t seq, int32_t token) {
     int rc = check_slot(c, seq, "llma_set_pending");
     if (rc) return rc;
