@@ -306,10 +306,13 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, const GemmPlan 
 // the order of every sum is the same for any number of rows; with several feature tiles AND several
 // row tiles a wave takes two K slices one after the other (half the waves, twice the registers).
 // ---------------------------------------------------------------------------------------------
+#ifndef TK_TRACE
+#define TK_TRACE(slot)      // (timeline probe of the one-off microbenchmarks; nothing in the library build)
+#endif
 template <int NT, int FT>
 struct TileKShape {
     static constexpr int SL = (FT > 1 && NT > 1) ? 2 : 1;            // K slices per wave
-    static constexpr int MAX_THREADS = (FT > 1 && NT == 1) ? 1024 : 512;
+    static constexpr int MAX_THREADS = (NT == 1) ? 1024 : 512;     // one row tile: up to 16 waves of <= 128 registers
 };
 template <int NT, int EPI, bool SPLIT, int FT>
 __global__ __launch_bounds__((TileKShape<NT, FT>::MAX_THREADS)) void gemm_tilek_bf16(GemmArgs a) {
@@ -320,6 +323,7 @@ __global__ __launch_bounds__((TileKShape<NT, FT>::MAX_THREADS)) void gemm_tilek_
     constexpr int PL = SPLIT ? 2 : 1;
     extern __shared__ f32x4 red[];                 // [S][AT][NT][64], then rstd[16*NT] floats
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, S = (blockDim.x >> 6) * SL;
+    TK_TRACE(0);
     // llma_generate launches k + 1 rows in every step; how many of them carry a token (1 + the
     // drafts the trigger found) is only known on the device.  The dead rows cost nothing here:
     // their lanes re-read the first row's operands and the epilogue skips them.
@@ -451,6 +455,7 @@ __global__ __launch_bounds__((TileKShape<NT, FT>::MAX_THREADS)) void gemm_tilek_
         while (ks < ks1) {
             if (ks + UB < ks1) issue(ks + UB, avB, bvB);
             compute(ks, avA, bvA);
+            TK_TRACE(1);
             ks += UB;
             if (ks >= ks1) break;
             if (ks + UB < ks1) issue(ks + UB, avA, bvA);
@@ -463,6 +468,7 @@ __global__ __launch_bounds__((TileKShape<NT, FT>::MAX_THREADS)) void gemm_tilek_
 #pragma unroll
             for (int t = 0; t < NT; ++t) red[((slice * AT + i) * NT + t) * 64 + lane] = acc[i][t];
     }
+    TK_TRACE(2);
     __syncthreads();
     if (!finisher) return;
     f32x4 sum[TILES][NT];
@@ -475,6 +481,7 @@ __global__ __launch_bounds__((TileKShape<NT, FT>::MAX_THREADS)) void gemm_tilek_
             sum[i][t] = v;
         }
     gemm_epilogue<NT, EPI, TILES>(a, p, my_task, lane, sum, rstd_s, in);
+    TK_TRACE(3);
 }
 
 template <int NT, int EPI, int FT>
@@ -534,8 +541,10 @@ __device__ __forceinline__ void offset_rows(GemmArgs &a, const GemmPlan &p, int 
 }
 
 #define PANEL_KC 2          // k-steps per LDS chunk
+// (four or more weight tiles per wave: accumulators for up to 9 row tiles each need the whole register
+//  file of a SIMD lane, 512 registers, i.e. one wave per SIMD; otherwise two)
 template <int RT, int EPI, int FT, int WV>
-__global__ __launch_bounds__(WV * 64, 2) void gemm_panel_bf16(GemmArgs a0) {
+__global__ __launch_bounds__(WV * 64, (FT * (EPI == EPI_SWIGLU ? 2 : 1) >= 4 ? 1 : 2)) void gemm_panel_bf16(GemmArgs a0) {
     constexpr int NTHR = WV * 64;
     constexpr int TILES = (EPI == EPI_SWIGLU) ? 2 : 1;
     constexpr int AT = FT * TILES;
@@ -769,11 +778,15 @@ static void launch_panel_cfg(const GemmArgs &a, hipStream_t st) {
 }
 
 // prompt-processing GEMM over any number of rows (needs a.rstd_in for the norm-scaled epilogues).
-// A workgroup owns 4 waves x FT feature tiles (FT = 2; SwiGLU: one gate/up pair) and RT row tiles,
-// RT = 5..8; two such workgroups fit a compute unit (their chunk barriers fall at different times,
-// which keeps the MFMA pipe busier than one workgroup of 8 waves did), so the launch runs in rounds
-// of 2 n_cu workgroups and the row-block height that needs the least rounds x height wins (1535 rows
-// on 256 units: 6, where QKV is 3.0 rounds instead of 2.25 and O / down exactly 1.0 instead of 0.75).
+// A workgroup owns WV waves x FT feature tiles (FT = 2; SwiGLU: one gate/up pair) and RT row tiles.
+// Prompt passes: WV = 4, RT = 5..8, two workgroups per compute unit (their chunk barriers fall at
+// different times, which keeps the MFMA pipe busier than one workgroup of 8 waves did); batched steps
+// (split-K): WV = 8, RT = 5..9, one workgroup per compute unit.  A launch runs in rounds of that many
+// workgroups; a round costs about RT + 3 (the weight stream and chunk barriers of a workgroup do not
+// shrink with its height), and the height with the least rounds x (RT + 3) wins: 1535 prompt rows: 6
+// (QKV 3.0 rounds instead of 2.25, O / down exactly 1.0); 144 rows of a batched step: 9 for QKV and
+// gate/up (one row block, the weights pass once: 64 -> 51 us, 104 -> 82 us), 5 for O and down (two row
+// blocks fill the 256 compute units, one would leave half of them idle: 28 vs 33 us, 47 vs 58 us).
 template <int EPI, int FT, int WV>
 static void launch_panel_wv(const GemmArgs &a, hipStream_t st) {
     static int n_cu = 0;
@@ -787,15 +800,20 @@ static void launch_panel_wv(const GemmArgs &a, hipStream_t st) {
     const int fb = ((a.plan.tasks + WV * FT - 1) / (WV * FT) + 7) / 8 * 8;
     const int row_tiles = (a.rows + 15) / 16;
     const int ns = a.ksplit > 1 ? a.ksplit : 1;
-    auto cost = [&](int rt) { return (long)((fb * ((row_tiles + rt - 1) / rt) * ns + slots - 1) / slots) * rt; };
-    int best = 8;
-    for (int rt = 7; rt >= 5; --rt)
-        if (cost(rt) < cost(best)) best = rt;
+    auto cost = [&](int rt) { return (long)((fb * ((row_tiles + rt - 1) / rt) * ns + slots - 1) / slots) * (rt + 3); };
+    constexpr int RT_MAX = (WV == 8) ? 9 : 8;            // (9 row tiles of accumulators need the 8-wave form's register budget)
+    int best = 5;
+    for (int rt = 6; rt <= RT_MAX; ++rt)
+        if (cost(rt) <= cost(best)) best = rt;            // (ties: fewer, taller row blocks stream the weights less often)
     switch (best) {
         case 5: launch_panel_cfg<5, EPI, FT, WV>(a, st); break;
         case 6: launch_panel_cfg<6, EPI, FT, WV>(a, st); break;
         case 7: launch_panel_cfg<7, EPI, FT, WV>(a, st); break;
-        default: launch_panel_cfg<8, EPI, FT, WV>(a, st); break;
+        case 8: launch_panel_cfg<8, EPI, FT, WV>(a, st); break;
+        default:
+            if constexpr (WV == 8) launch_panel_cfg<9, EPI, FT, WV>(a, st);
+            else launch_panel_cfg<8, EPI, FT, WV>(a, st);
+            break;
     }
     if (a.ksplit > 1) launch_splitk_finish<EPI>(a, st);
 }
