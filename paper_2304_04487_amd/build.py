@@ -35,15 +35,32 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build(verbose: bool = True) -> str:
+# stand-alone measurement tool (csrc/microbench.hip): the same source twice, the second time with the
+# per-wave time stamps compiled into the GEMM kernels
+TOOLS = {"llma_microbench": [], "llma_microbench_timeline": ["-DMICROBENCH_TIMELINE"]}
+
+
+def _tool(name: str) -> str:
+    out = os.path.join(HERE, "tools", name)
+    cmd = [_hipcc(), *[f for f in FLAGS if f != "-fPIC"], *TOOLS[name], os.path.join(CSRC, "microbench.hip"), "-o", out]
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed on {name}:\n" + "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l))
+    return out
+
+
+def build(verbose: bool = True, tools: bool = True) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    os.makedirs(os.path.join(HERE, "tools"), exist_ok=True)
+    with ThreadPoolExecutor(max_workers=6) as ex:
+        tool_jobs = [ex.submit(_tool, t) for t in TOOLS] if tools else []
         objs = list(ex.map(_compile, SOURCES))
+        built_tools = [j.result() for j in tool_jobs]
     subprocess.check_call([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
     if verbose:
-        print(f"built {LIB}")
+        print(f"built {LIB}" + "".join(f"\nbuilt {t}" for t in built_tools))
     return LIB
 
 
 if __name__ == "__main__":
-    build()
+    build(tools="--no-tools" not in sys.argv)
