@@ -288,7 +288,7 @@ def main():
     t0 = time.time()
     ctx = llma.Context(cfg, w, max_seq=wl.prompt_len + wl.max_new + 64, max_batch=1, max_k=max(18 if args.grid else 16, k))
     del w
-    log(f"[bench] context created in {time.time() - t0:.1f}s, {ctx.device_bytes() / 1e9:.2f} GB on device")
+    log(f"[bench] context created in {time.time() - t0:.1f}s, {ctx.device_bytes() / 1e9:.2f} GB on device; {ctx.describe()}")
 
     if args.profile_steps:
         # what one decoding step launches, in isolation, for counter collection: the cache content does

@@ -233,6 +233,9 @@ int llma_get_kernel_timing(llma_ctx *ctx, int64_t *launches, double *total_ms);
  * them.  The activations are whatever the context's scratch holds; outputs go to scratch.
  * bf16 models only.  Synchronises the stream.  For the roofline figure of the benchmark. */
 int llma_time_ffn_gemm(llma_ctx *ctx, int32_t rows, int32_t reps, double *mean_us);
+/* One line of text about what the context tuned at creation (the work division of the decoding
+ * GEMMs, which llma_create picks by timing; it changes no result).  buf: HOST, cap bytes. */
+int llma_describe(const llma_ctx *ctx, char *buf, int32_t cap);
 /* Device bytes the context holds (weights, KV cache, scratch). */
 int64_t llma_device_bytes(const llma_ctx *ctx);
 

@@ -25,6 +25,7 @@ EXPORTS = [
     "llma_set_pending", "llma_kv_import", "llma_find_trigger", "llma_verify_step",
     "llma_verify_step_batch", "llma_generate", "llma_generate_batch", "llma_set_logits_dump", "llma_set_option",
     "llma_get_kernel_timing", "llma_time_ffn_gemm", "llma_device_bytes", "llma_find_trigger_static", "llma_truncate",
+    "llma_describe",
 ]
 LLMA_TRIGGER_STATIC_MAX_REF = 1 << 20
 
@@ -86,6 +87,7 @@ def load_library() -> ctypes.CDLL:
     lib.llma_set_option.argtypes = [vp, c_int32, c_int32]
     lib.llma_get_kernel_timing.argtypes = [vp, POINTER(c_int64), POINTER(c_double)]
     lib.llma_time_ffn_gemm.argtypes = [vp, c_int32, c_int32, POINTER(c_double)]
+    lib.llma_describe.argtypes = [vp, c_char_p, c_int32]
     lib.llma_device_bytes.argtypes = [vp]
     lib.llma_device_bytes.restype = c_int64
     _lib = lib
@@ -290,6 +292,11 @@ class Context:
         us = c_double()
         self._ck(self.lib.llma_time_ffn_gemm(self._h, rows, reps, byref(us)))
         return us.value
+
+    def describe(self) -> str:
+        buf = ctypes.create_string_buffer(512)
+        self._ck(self.lib.llma_describe(self._h, buf, 512))
+        return buf.value.decode()
 
     def device_bytes(self) -> int:
         return int(self.lib.llma_device_bytes(self._h))

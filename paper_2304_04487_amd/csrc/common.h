@@ -82,8 +82,10 @@ struct GemmPlan {
     int N, K;        // logical shape (SWIGLU: N = d_ffn, the matrix has 2N rows)
     int KSp;         // k-steps (of 32) per feature tile
     int tasks;       // feature tiles (SWIGLU: gate/up tile pairs)
-    int tk_ft;       // tile-K kernel: feature tiles per workgroup
-    int tk_waves;    //   and K slices (= waves, or half as many waves taking two slices each)
+    int tiles_per_task;   // 2 for the fused gate/up matrix, else 1
+    int tk_ft[3];    // tile-K kernel: feature tiles (SWIGLU: pairs) per workgroup for 1, 2, 3 row tiles.  Work division
+                     //   only -- every tile's sum is the same whatever the value -- so it may be tuned per device
+    int tk_waves;    //   and K slices (= waves, or half as many waves taking two slices each): fixes the order of the sums
     int n_split;     // panel kernel, batched steps: ranges the K axis is cut into (1 = no split)
 };
 

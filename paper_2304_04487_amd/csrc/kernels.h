@@ -4,6 +4,8 @@
 
 // ---- bf16 path (kernels_bf16.hip)
 GemmPlan make_gemm_plan(int N, int K, int tiles_per_task);
+bool tilek_ft_valid(const GemmPlan &p, int nt, int ft);     // can the decoding GEMM run ft feature tiles per workgroup at nt row tiles?
+int tilek_ft_default(const GemmPlan &p, int nt);
 void launch_pack_weight(const void *src, void *dst, int N, int K, int KSp, int rope_dh, int d, hipStream_t st);
 void launch_kv_import_bf16(const void *k, const void *v, void *kh, void *kl, void *vh, void *vl, int H, int len, int dh,
                            int max_seq, hipStream_t st);

@@ -304,14 +304,15 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, const GemmPlan 
 // workgroups); the waves' partial sums meet in LDS and are added in wave order; the first FT
 // waves run the fused epilogue.  FT and the number of K slices depend on the matrix shape only, so
 // the order of every sum is the same for any number of rows; with several feature tiles AND several
-// row tiles a wave takes two K slices one after the other (half the waves, twice the registers).
+// row tiles (more than four tile pairs in all) a wave takes two K slices one after the other (half the
+// waves, twice the registers).
 // ---------------------------------------------------------------------------------------------
 #ifndef TK_TRACE
 #define TK_TRACE(slot)      // (timeline probe of the one-off microbenchmarks; nothing in the library build)
 #endif
 template <int NT, int FT>
 struct TileKShape {
-    static constexpr int SL = (FT > 1 && NT > 1) ? 2 : 1;            // K slices per wave
+    static constexpr int SL = (FT > 1 && NT > 1 && FT * NT > 4) ? 2 : 1;   // K slices per wave
     static constexpr int MAX_THREADS = (NT == 1) ? 1024 : 512;     // one row tile: up to 16 waves of <= 128 registers
 };
 template <int NT, int EPI, bool SPLIT, int FT>
@@ -484,11 +485,31 @@ __global__ __launch_bounds__((TileKShape<NT, FT>::MAX_THREADS)) void gemm_tilek_
     TK_TRACE(3);
 }
 
+// Which (feature tiles per workgroup) values the tile-K kernel can run for a matrix at nt row tiles: the
+// waves' partial sums (K slices x tiles x row tiles KiB) must fit LDS, every finishing wave needs a tile,
+// and a single-tile workgroup with several row tiles runs one slice per wave (at most 8 waves).
+bool tilek_ft_valid(const GemmPlan &p, int nt, int ft) {
+    if (ft < 1 || ft > 4 || nt < 1 || nt > 3) return false;
+    const int tiles = p.tiles_per_task * ft;
+    const int sl = (ft > 1 && nt > 1 && ft * nt > 4) ? 2 : 1, waves = p.tk_waves / sl;     // (TileKShape::SL)
+    if (waves < ft || waves * 64 > (nt == 1 ? 1024 : 512)) return false;
+    if (p.tiles_per_task == 2 && ft > 2) return false;
+    return (size_t)p.tk_waves * tiles * nt * 1024 + 256 <= 160 * 1024 - 1024;
+}
+int tilek_ft_default(const GemmPlan &p, int nt) {
+    const int want = (p.tiles_per_task == 2) ? 1 : (p.tk_waves == 16 ? 3 : 1);
+    for (int ft = want; ft <= 4; ++ft)
+        if (tilek_ft_valid(p, nt, ft)) return ft;
+    for (int ft = want - 1; ft >= 1; --ft)
+        if (tilek_ft_valid(p, nt, ft)) return ft;
+    return 1;
+}
+
 template <int NT, int EPI, int FT>
 static void launch_tilek(const GemmArgs &a, hipStream_t st) {
     constexpr int TILES = (EPI == EPI_SWIGLU) ? 2 : 1;
     const GemmPlan &p = a.plan;
-    const int S = (FT == 1 && p.tk_waves > 8) ? 8 : p.tk_waves;      // K slices (single-tile kernels are built for 8 waves)
+    const int S = p.tk_waves;                                        // K slices
     const int W = S / TileKShape<NT, FT>::SL;
     const size_t lds = (size_t)S * FT * TILES * NT * 1024 + 256;
     dim3 grid((p.tasks + FT - 1) / FT), block(W * 64);
@@ -505,8 +526,12 @@ static void launch_tilek(const GemmArgs &a, hipStream_t st) {
 
 template <int NT, int EPI>
 static void launch_gemm_nt_epi(const GemmArgs &a, hipStream_t st) {
-    if (a.plan.tk_ft == 1) launch_tilek<NT, EPI, 1>(a, st);
-    else launch_tilek<NT, EPI, 3>(a, st);               // make_gemm_plan() knows 1 and 3 only
+    switch (tilek_ft_valid(a.plan, NT, a.plan.tk_ft[NT - 1]) ? a.plan.tk_ft[NT - 1] : tilek_ft_default(a.plan, NT)) {
+        case 1: launch_tilek<NT, EPI, 1>(a, st); break;
+        case 2: launch_tilek<NT, EPI, 2>(a, st); break;
+        case 3: launch_tilek<NT, EPI, 3>(a, st); break;
+        default: launch_tilek<NT, EPI, 4>(a, st); break;
+    }
 }
 
 template <int NT>
@@ -853,9 +878,12 @@ GemmPlan make_gemm_plan(int N, int K, int tiles_per_task) {
     p.N = N; p.K = K;
     p.KSp = K / 32;
     p.tasks = N / 16;
-    // (waves x tiles per workgroup <= 48 keeps the wave-order reduction of three row tiles inside LDS)
-    p.tk_ft = (tiles_per_task == 2) ? 1 : (p.tasks >= 640 ? 3 : 1);
-    p.tk_waves = p.tk_ft > 1 ? 16 : 8;
+    // K slices: 16 for matrices of 640+ tiles (QKV, LM head), else 8; feature tiles per workgroup: three
+    // resp. one by default (the values measured fastest on the 7B shapes), re-tuned per context by timing
+    // (llma_create), which cannot change any result
+    p.tiles_per_task = tiles_per_task;
+    p.tk_waves = (tiles_per_task != 2 && p.tasks >= 640) ? 16 : 8;
+    for (int nt = 1; nt <= 3; ++nt) p.tk_ft[nt - 1] = tilek_ft_default(p, nt);
     // split-K form of the panel kernel: enough ranges that feature blocks x ranges is about 200
     // workgroups per row block (2..8, a function of the matrix only, so a row's sums do not depend on
     // how many rows share the step)

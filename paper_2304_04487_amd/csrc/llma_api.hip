@@ -169,6 +169,7 @@ static int take_matrix(llma_ctx *c, void **dst, const void *src, int N, int K, i
     return LLMA_OK;
 }
 
+static int autotune_tilek(llma_ctx *c);
 static int create_impl(llma_ctx *c, const llma_weights *w) {
     const llma_model_cfg &g = c->cfg;
     const int L = g.n_layers, d = g.d_model, F = g.d_ffn, V = g.vocab, H = g.n_heads, dh = g.head_dim;
@@ -312,6 +313,98 @@ static int create_impl(llma_ctx *c, const llma_weights *w) {
     HIP_TRY(c, hipEventCreateWithFlags(&c->cnt_ev[1], hipEventDisableTiming));
     HIP_TRY(c, hipStreamSynchronize(c->st));
     HIP_TRY(c, hipGetLastError());
+    return autotune_tilek(c);
+}
+
+// ------------------------------------------------------------------------------------------------
+// decoding-step GEMM arguments outside a forward (tuning, timing): matrix `which` of layer `layer`
+// (0 QKV, 1 O, 2 gate/up, 3 down, 4 LM head) over `rows` rows of whatever the scratch planes hold
+// ------------------------------------------------------------------------------------------------
+static GemmArgs step_gemm_args(llma_ctx *c, int which, int layer, int rows) {
+    const llma_model_cfg &g = c->cfg;
+    GemmArgs ga{};
+    ga.rows = rows; ga.split = c->opt_split; ga.eps = g.rms_eps; ga.rstd_in = c->rstd;
+    ga.ssq_tiles = g.d_model / 16; ga.H = g.n_heads; ga.dh = g.head_dim; ga.max_seq = c->seq_cap; ga.nx_KSp = c->plan_qkv.KSp;
+    switch (which) {
+        case 0:
+            ga.W = c->wqkv[layer]; ga.plan = c->plan_qkv; ga.Xhi = c->xhi; ga.Xlo = c->xlo; ga.epi = EPI_QKV; ga.ssq_in = c->ssq;
+            ga.row_pos = c->s.row_pos; ga.row_slot = c->s.row_slot; ga.row_cs = c->s.row_cs; ga.q_hi = c->q; ga.q_lo = c->q_lo;
+            ga.k_hi = c->kc[layer]; ga.k_lo = c->kc_lo[layer]; ga.v_hi = c->vc[layer]; ga.v_lo = c->vc_lo[layer];
+            break;
+        case 1:
+            ga.W = c->wo[layer]; ga.plan = c->plan_o; ga.Xhi = c->att_hi; ga.Xlo = c->att_lo; ga.epi = EPI_RESID; ga.out = c->h;
+            ga.gain = c->n2[layer]; ga.nx_hi = c->xhi; ga.nx_lo = c->xlo; ga.ssq_out = c->ssq;
+            break;
+        case 2:
+            ga.W = c->wgu[layer]; ga.plan = c->plan_gu; ga.Xhi = c->xhi; ga.Xlo = c->xlo; ga.epi = EPI_SWIGLU; ga.ssq_in = c->ssq;
+            ga.act_hi = c->act_hi; ga.act_lo = c->act_lo; ga.act_KSp = c->plan_down.KSp;
+            break;
+        case 3:
+            ga.W = c->wd[layer]; ga.plan = c->plan_down; ga.Xhi = c->act_hi; ga.Xlo = c->act_lo; ga.epi = EPI_RESID; ga.out = c->h;
+            ga.gain = c->n1[layer]; ga.nx_hi = c->xhi; ga.nx_lo = c->xlo; ga.ssq_out = c->ssq;
+            break;
+        default:
+            ga.W = c->lm_head; ga.plan = c->plan_lm; ga.Xhi = c->xhi; ga.Xlo = c->xlo; ga.epi = EPI_LMHEAD; ga.ssq_in = c->ssq;
+            ga.out = nullptr; ga.pval = c->pval; ga.pidx = c->pidx; ga.n_part = c->n_part;
+            break;
+    }
+    return ga;
+}
+
+// How many feature tiles a workgroup of the decoding GEMM takes is pure work division (a tile's sums are
+// the same for any value), and which value streams a matrix fastest depends on how its tile count falls
+// on the device's compute units (7B: one tile per workgroup for the 256-tile O / down matrices; 13B, 320
+// tiles: two, 35.6 -> 27.0 us for down; QKV 960 tiles: four, 34.0 -> 26.1 us).  So it is measured: every
+// admissible value, for 1 / 17 / 33 rows (one, two, three row tiles), on the context's own matrices and
+// zeroed scratch, a few dozen launches each; a value has to beat the default by 3 % to replace it.
+static int autotune_tilek(llma_ctx *c) {
+    if (!c->bf16 || getenv("LLMA_NO_AUTOTUNE") != nullptr) return LLMA_OK;
+    const llma_model_cfg &g = c->cfg;
+    GemmPlan *plans[5] = {&c->plan_qkv, &c->plan_o, &c->plan_gu, &c->plan_down, &c->plan_lm};
+    if (const char *forced = getenv("LLMA_TILEK_FT")) {       // tests: this many tiles per workgroup wherever the kernel admits it
+        const int ft = atoi(forced);
+        for (GemmPlan *p : plans)
+            for (int nt = 1; nt <= 3; ++nt)
+                if (tilek_ft_valid(*p, nt, ft)) p->tk_ft[nt - 1] = ft;
+        return LLMA_OK;
+    }
+    const int step_rows = g.max_batch * (g.max_k + 1);
+    hipEvent_t e0, e1;
+    HIP_TRY(c, hipEventCreate(&e0));
+    HIP_TRY(c, hipEventCreate(&e1));
+    const int reps = g.n_layers < 8 ? 16 : (2 * g.n_layers < 48 ? 2 * g.n_layers : 48);
+    for (int which = 0; which < 5; ++which)
+        for (int nt = 1; nt <= 3; ++nt) {
+            const int rows = nt == 1 ? 1 : 16 * (nt - 1) + 1;
+            if (rows > step_rows || rows > 48) continue;                  // this context never launches that many row tiles
+            GemmPlan &p = *plans[which];
+            const int dflt = p.tk_ft[nt - 1];
+            float best_us = 0.f, dflt_us = 0.f;
+            int best = dflt;
+            for (int ft = 1; ft <= 4; ++ft) {
+                if (!tilek_ft_valid(p, nt, ft)) continue;
+                p.tk_ft[nt - 1] = ft;
+                float ms = 0.f;
+                for (int pass = 0; pass < 2; ++pass) {                    // pass 0 warms up
+                    const int n = pass ? reps : 3;
+                    HIP_TRY(c, hipEventRecord(e0, c->st));
+                    for (int r = 0; r < n; ++r) {
+                        GemmArgs ga = step_gemm_args(c, which, r % g.n_layers, rows);
+                        if (!launch_gemm_bf16(ga, c->st)) return fail(c, LLMA_E_INVAL, "autotune: launch refused");
+                    }
+                    HIP_TRY(c, hipEventRecord(e1, c->st));
+                    HIP_TRY(c, hipEventSynchronize(e1));
+                    HIP_TRY(c, hipEventElapsedTime(&ms, e0, e1));
+                }
+                const float us = ms * 1e3f / reps;
+                if (ft == dflt) dflt_us = us;
+                if (best_us == 0.f || us < best_us) { best_us = us; best = ft; }
+            }
+            p.tk_ft[nt - 1] = (dflt_us > 0.f && best_us < 0.97f * dflt_us) ? best : dflt;
+        }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    HIP_TRY(c, hipGetLastError());
     return LLMA_OK;
 }
 
@@ -355,6 +448,17 @@ extern "C" int llma_destroy(llma_ctx *c) {
 
 extern "C" const char *llma_last_error(const llma_ctx *c) { return c ? c->err.c_str() : g_err.c_str(); }
 extern "C" int64_t llma_device_bytes(const llma_ctx *c) { return c ? c->dev_bytes : 0; }
+
+extern "C" int llma_describe(const llma_ctx *c, char *buf, int32_t cap) {
+    if (!c || !buf || cap < 1) return LLMA_E_INVAL;
+    if (!c->bf16) { snprintf(buf, (size_t)cap, "fp32 path (plain vector-ALU kernels, nothing tuned)"); return LLMA_OK; }
+    const GemmPlan *pl[5] = {&c->plan_qkv, &c->plan_o, &c->plan_gu, &c->plan_down, &c->plan_lm};
+    const char *nm[5] = {"qkv", "o", "gate_up", "down", "lm_head"};
+    int n = snprintf(buf, (size_t)cap, "decoding GEMM, feature tiles per workgroup at 1/2/3 row tiles (K slices):");
+    for (int i = 0; i < 5 && n > 0 && n < cap; ++i)
+        n += snprintf(buf + n, (size_t)(cap - n), " %s %d/%d/%d (%d)", nm[i], pl[i]->tk_ft[0], pl[i]->tk_ft[1], pl[i]->tk_ft[2], pl[i]->tk_waves);
+    return LLMA_OK;
+}
 
 // ------------------------------------------------------------------------------------------------
 // the forward over the rows described by ctx->s.row_* (paper: Eq. 3)
@@ -962,11 +1066,7 @@ extern "C" int llma_time_ffn_gemm(llma_ctx *c, int32_t rows, int32_t reps, doubl
     if (rows < 1 || rows > 48 || rows > c->cfg.max_batch * (c->cfg.max_k + 1) || reps < 1 || reps > 100000)
         return fail(c, LLMA_E_RANGE, "llma_time_ffn_gemm: rows %d (1..min(48, max_batch (max_k + 1))) or reps %d (1..100000) out of range", rows, reps);
     const llma_model_cfg &g = c->cfg;
-    GemmArgs ga{};
-    ga.rows = rows; ga.split = c->opt_split; ga.eps = g.rms_eps; ga.rstd_in = c->rstd;
-    ga.ssq_tiles = g.d_model / 16; ga.H = g.n_heads; ga.dh = g.head_dim; ga.max_seq = c->seq_cap; ga.nx_KSp = c->plan_qkv.KSp;
-    ga.plan = c->plan_gu; ga.Xhi = c->xhi; ga.Xlo = c->xlo; ga.epi = EPI_SWIGLU; ga.ssq_in = c->ssq;
-    ga.act_hi = c->act_hi; ga.act_lo = c->act_lo; ga.act_KSp = c->plan_down.KSp;
+    GemmArgs ga = step_gemm_args(c, 2, 0, rows);
     hipEvent_t e0, e1;
     HIP_TRY(c, hipEventCreate(&e0));
     HIP_TRY(c, hipEventCreate(&e1));

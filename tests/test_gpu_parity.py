@@ -461,3 +461,41 @@ def test_step_graphs_of_prompt_passes_with_256_rows_apart(llma):
         assert st0 == want[i % 2][0] and st1 == want[i % 2][1], (i, st0, st1)
         assert np.array_equal(lg, want[i % 2][2]), f"round {i // 2}, case {i % 2}: logits differ from the eager path"
     ctx.close()
+
+
+def test_work_division_of_the_decoding_gemm_changes_no_bit(llma, monkeypatch):
+    """llma_create times how many feature tiles a workgroup of the decoding GEMMs should take and keeps
+    the fastest; that is work division only.  Contexts forced to 1, 2, 3 and 4 tiles per workgroup
+    (wherever the kernel admits the value) must produce bit-identical logits and states for steps of
+    one, two and three row tiles, and the same tokens from llma_generate."""
+    cfg = synth.ModelCfg("ftmix", 2, 1024, 8, 128, 2816, 12000, "bf16")       # 192 QKV tiles, 64 O tiles, 176 gate/up pairs, 750 LM-head tiles
+    w = synth.make_weights(cfg, 17, gain_jitter=0.2)
+    prompt = synth.uniform_tokens(17, 1, 70, cfg.vocab)
+    drafts = {k: synth.uniform_tokens(17, 10 + k, k, cfg.vocab).tolist() for k in (0, 5, 20, 32)}
+    ref = np.concatenate([prompt[10:40], synth.uniform_tokens(17, 3, 30, cfg.vocab)])
+    results = {}
+    for ft in (0, 1, 2, 3, 4):
+        if ft:
+            monkeypatch.setenv("LLMA_TILEK_FT", str(ft))
+        else:
+            monkeypatch.delenv("LLMA_TILEK_FT", raising=False)          # the timed choice
+        ctx = llma.Context(cfg, w, max_seq=320, max_batch=1, max_k=32)
+        desc = ctx.describe()
+        out = []
+        ctx.enable_logits_dump(33)
+        ctx.prefill(prompt)
+        for k in (0, 5, 20, 32):
+            na, nxt, _ = ctx.verify_step(drafts[k])
+            out.append((na, nxt, ctx.get_state(), ctx.logits(k + 1).copy()))
+        ctx.disable_logits_dump()
+        toks, trace = ctx.generate(prompt, ref, [0, len(ref)], 1, 8, 40)
+        results[ft] = (out, toks, trace, desc)
+        ctx.close()
+    monkeypatch.delenv("LLMA_TILEK_FT", raising=False)
+    assert len({results[ft][3] for ft in (1, 2, 3, 4)}) == 4, "the forced values did not reach the plans"
+    base = results[1]
+    for ft in (0, 2, 3, 4):
+        for (na, nxt, st, lg), (na0, nxt0, st0, lg0) in zip(results[ft][0], base[0]):
+            assert (na, nxt, st) == (na0, nxt0, st0)
+            assert np.array_equal(lg, lg0), f"{results[ft][3]}: logits differ from the one-tile division"
+        assert np.array_equal(results[ft][1], base[1]) and results[ft][2] == base[2]
