@@ -135,7 +135,8 @@ struct AttnArgs {
     int slot_const;         // >= 0: the single sequence's slot (saves a dependent load); -1: read batch_slots
     int n_seqs, m;          // rows per sequence
     int H, dh, max_seq;
-    int n_chunks;           // launched chunks (upper bound over the batch)
+    int n_chunks;           // launched chunks (upper bound over the batch); the partials' count per (sequence, head)
+    int part_span;          // key positions one partial covers (ATTN_CHUNK, or a whole number of chunks); set by the launcher
     const int *rows_live;   // may be null: device int, rows 0 .. *rows_live of the (single) sequence carry tokens
     const int *lo_from;     // may be null: [max_batch] device ints, positions below lo_from[slot] have all-zero lo planes (imported bf16 caches)
     int n_rblocks;          // row blocks per sequence (set by the launcher)

@@ -1132,6 +1132,198 @@ __global__ __launch_bounds__(256, (COMPACT ? 2 : 1)) void attn_bf16_kernel(AttnA
     attn_chunk_body<DH, NTQ, KVS, LIVE, COMPACT>(a, sm, sl, so);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Wide batched steps (several sequences, more than 48 rows in all; their GEMMs already add in an
+// order of their own): a workgroup walks ATTN_WALK_CHUNKS consecutive chunks of one (sequence, head)
+// instead of one.  Every chunk is computed like above -- four waves x 32 positions, all K/V blocks of
+// the chunk requested at once, (max, sum, O) per wave merged through LDS in wave order -- and the merged
+// chunk is folded into a running (max, sum, O) held in registers, in chunk order; one partial per
+// walk goes to the combine kernel.  Four times fewer workgroups, partials and combine work than one
+// chunk per workgroup (16 sequences x 4096 positions: 16384 -> 4096 workgroups per layer).  Chunks
+// that lie entirely below lo_from[slot] (imported bf16 caches: all-zero lo planes) skip the lo planes.
+// ---------------------------------------------------------------------------------------------
+#define ATTN_WALK_CHUNKS 4
+template <int DH, int NTQ, bool KVS>
+__global__ __launch_bounds__(256, 2) void attn_walk_bf16_kernel(AttnArgs a) {
+    constexpr int KSTEPS = DH / 32, DT = DH / 16;
+    constexpr int RQ = NTQ * 16;
+    constexpr int RS = (NTQ == 3) ? ATTN_COMPACT_ROWS : RQ;          // rows the merge buffer holds (a step has at most 33 per sequence)
+    constexpr int OWN = (RS * (DH / 4) + 255) / 256;                  // merged output elements (float4) per thread
+    __shared__ float sm[4][RQ], sl[4][RQ];
+    __shared__ float so[4][RS][DH + 4];
+    const int h = blockIdx.y, b = blockIdx.z / a.n_rblocks, rb = blockIdx.z % a.n_rblocks;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 15, g = lane >> 4;
+    const int slot = a.batch_slots[b];
+    const int T = a.T[slot];
+    const int lo_from = (KVS && a.lo_from != nullptr) ? a.lo_from[slot] : 0;
+    const int m = a.m, j0 = rb * RQ;
+    if (j0 >= m) return;
+    const int m_blk = (m - j0 < RQ) ? m - j0 : RQ;
+    const int kv_len = T + j0 + m_blk;                               // positions the block's last row can see
+    const int c0 = blockIdx.x * ATTN_WALK_CHUNKS;
+    if (c0 * ATTN_CHUNK >= kv_len) return;                           // uniform for the workgroup
+    const int c_need = (kv_len + ATTN_CHUNK - 1) / ATTN_CHUNK;
+    const int c1 = c0 + ATTN_WALK_CHUNKS < c_need ? c0 + ATTN_WALK_CHUNKS : c_need;
+    // chunks below c_lo lie entirely inside an imported bf16 cache: single plane
+    int c_lo = KVS ? lo_from / ATTN_CHUNK : c1;
+    c_lo = c_lo < c0 ? c0 : (c_lo > c1 ? c1 : c_lo);
+    const int d_model = a.H * DH;
+    const size_t head_base = ((size_t)slot * a.H + h) * (size_t)a.max_seq * DH;
+    const bf16_t *kh = (const bf16_t *)a.Khi + head_base, *kl = (const bf16_t *)a.Klo + head_base;
+    const bf16_t *vh = (const bf16_t *)a.Vhi + head_base, *vl = (const bf16_t *)a.Vlo + head_base;
+
+    f32x4 acc_run[OWN];
+    float M_run[OWN];
+#pragma unroll
+    for (int i = 0; i < OWN; ++i) { acc_run[i] = (f32x4){0.f, 0.f, 0.f, 0.f}; M_run[i] = LLMA_NEG_INF; }
+    float M_row = LLMA_NEG_INF, L_row = 0.f;                         // thread j < m_blk: row j's running max / sum
+    for (int c = c0; c < c1; ++c) {
+        const int key0 = c * ATTN_CHUNK + wave * 32;
+        const bool active = key0 < kv_len;                           // uniform for the wave
+        const bool use_lo = KVS && c >= c_lo;                        // uniform for the workgroup
+        u32x4 ka[2][KSTEPS], kb[2][KSTEPS], va[DT], vb[DT];
+        if (active) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int s = 0; s < KSTEPS; ++s) {
+                    const size_t off = (size_t)(key0 / 16 + t) * (16 * DH) + s * 512 + lane * 8;
+                    ka[t][s] = *(const u32x4 *)(kh + off);
+                    if (KVS && use_lo) kb[t][s] = *(const u32x4 *)(kl + off);
+                }
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                const size_t off = (size_t)(key0 / 32) * (32 * DH) + dt * 512 + lane * 8;
+                va[dt] = *(const u32x4 *)(vh + off);
+                if (KVS && use_lo) vb[dt] = *(const u32x4 *)(vl + off);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < NTQ; ++q) {
+            const int j = j0 + q * 16 + n;
+            const bool valid = j < m;
+            float mrow = LLMA_NEG_INF, lsum = 0.f;
+            f32x4 o[DT];
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) o[dt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            if (active && j0 + q * 16 < m) {                         // (a row tile past the block's rows: nothing to do, uniform)
+                const int rpos = valid ? T + j : -1;
+                const int r = b * m + (valid ? j : j0);
+                u32x4 qh[KSTEPS], ql[KSTEPS];
+#pragma unroll
+                for (int s = 0; s < KSTEPS; ++s) {
+                    const size_t off = xtile_off(r, h * DH + s * 32 + g * 8, d_model / 32);
+                    qh[s] = *(const u32x4 *)((const bf16_t *)a.Qhi + off);
+                    ql[s] = *(const u32x4 *)((const bf16_t *)a.Qlo + off);
+                }
+                float sv[8];
+                float mx = LLMA_NEG_INF;
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int s = 0; s < KSTEPS; ++s) {
+                        acc = mfma16x16x32(ka[t][s], qh[s], acc);
+                        acc = mfma16x16x32(ka[t][s], ql[s], acc);
+                        if (KVS && use_lo) acc = mfma16x16x32(kb[t][s], qh[s], acc);
+                    }
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        const int key = key0 + t * 16 + 4 * g + r4;
+                        float v = acc[r4] * a.scale;
+                        v = (key > rpos) ? LLMA_NEG_INF : v;
+                        sv[t * 4 + r4] = v;
+                        mx = fmaxf(mx, v);
+                    }
+                }
+                mx = fmaxf(mx, __shfl_xor(mx, 16));
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                float p[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    p[i] = (mx == LLMA_NEG_INF) ? 0.f : __expf(sv[i] - mx);
+                    lsum += p[i];
+                }
+                mrow = mx;
+                u32x2 h0, l0, h1, l1;
+                split4(p, h0, l0);
+                split4(p + 4, h1, l1);
+                const u32x4 ph = (u32x4){h0[0], h0[1], h1[0], h1[1]};
+                const u32x4 pl = (u32x4){l0[0], l0[1], l1[0], l1[1]};
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    o[dt] = mfma16x16x32(va[dt], ph, o[dt]);
+                    o[dt] = mfma16x16x32(va[dt], pl, o[dt]);
+                    if (KVS && use_lo) o[dt] = mfma16x16x32(vb[dt], ph, o[dt]);
+                }
+            }
+            // publish this wave's (max, sum, O) of the row tile
+            lsum += __shfl_xor(lsum, 16);
+            lsum += __shfl_xor(lsum, 32);
+            if (g == 0) { sm[wave][q * 16 + n] = mrow; sl[wave][q * 16 + n] = lsum; }
+            if (q * 16 + n < RS)
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) *(f32x4 *)&so[wave][q * 16 + n][dt * 16 + 4 * g] = o[dt];
+        }
+        __syncthreads();
+        // merge the four waves in wave order, then fold the chunk into the running state (chunk order)
+#pragma unroll
+        for (int i = 0; i < OWN; ++i) {
+            const int idx = threadIdx.x + 256 * i;
+            if (idx < m_blk * (DH / 4)) {
+                const int j = idx / (DH / 4), d4 = idx % (DH / 4);
+                float Mc = LLMA_NEG_INF;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) Mc = fmaxf(Mc, sm[w][j]);
+                if (Mc != LLMA_NEG_INF) {
+                    f32x4 accc = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) {
+                        const float mw = sm[w][j];
+                        const float sc = (mw == LLMA_NEG_INF) ? 0.f : __expf(mw - Mc);
+                        accc += *(const f32x4 *)&so[w][j][d4 * 4] * sc;
+                    }
+                    const float Mn = fmaxf(M_run[i], Mc);
+                    const float s_run = (M_run[i] == LLMA_NEG_INF) ? 0.f : __expf(M_run[i] - Mn);
+                    acc_run[i] = acc_run[i] * s_run + accc * __expf(Mc - Mn);
+                    M_run[i] = Mn;
+                }
+            }
+        }
+        if (threadIdx.x < m_blk) {
+            const int j = threadIdx.x;
+            float Mc = LLMA_NEG_INF;
+            for (int w = 0; w < 4; ++w) Mc = fmaxf(Mc, sm[w][j]);
+            if (Mc != LLMA_NEG_INF) {
+                float Lc = 0.f;
+                for (int w = 0; w < 4; ++w) {
+                    const float mw = sm[w][j];
+                    Lc += (mw == LLMA_NEG_INF) ? 0.f : sl[w][j] * __expf(mw - Mc);
+                }
+                const float Mn = fmaxf(M_row, Mc);
+                const float s_run = (M_row == LLMA_NEG_INF) ? 0.f : __expf(M_row - Mn);
+                L_row = L_row * s_run + Lc * __expf(Mc - Mn);
+                M_row = Mn;
+            }
+        }
+        __syncthreads();                                             // the merge buffers are written again by the next chunk
+    }
+    const size_t pbase = (((size_t)b * a.H + h) * a.n_chunks + blockIdx.x) * ((size_t)a.n_rblocks * RQ) + j0;
+#pragma unroll
+    for (int i = 0; i < OWN; ++i) {
+        const int idx = threadIdx.x + 256 * i;
+        if (idx < m_blk * (DH / 4)) {
+            const int j = idx / (DH / 4), d4 = idx % (DH / 4);
+            *(f32x4 *)(a.po + (pbase + j) * DH + d4 * 4) = acc_run[i];
+        }
+    }
+    if (threadIdx.x < m_blk) {
+        a.pm[pbase + threadIdx.x] = M_row;
+        a.pl[pbase + threadIdx.x] = L_row;
+    }
+}
+
 // merges the chunk partials of one (row, head): out = sum_c e^{m_c - M} O_c / sum_c e^{m_c - M} l_c,
 // over the chunks that contain positions <= the row's own, in chunk order; writes hi/lo tiled planes.
 // One thread per 4 output features; the partials of 16 chunks are in flight at a time.
@@ -1165,7 +1357,7 @@ __global__ void attn_combine_bf16_kernel(AttnArgs a, int rq) {
     loads_stay_above();
     if (j > live_last) return;                         // padding row of a generation step (its partials are stale: dropped)
     const int pos = T + j;
-    const int nc = pos / ATTN_CHUNK + 1;
+    const int nc = pos / a.part_span + 1;
     // running (max, sum, O) over the chunks in chunk order
     float M = LLMA_NEG_INF, L = 0.f;
     f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -1367,6 +1559,17 @@ static void launch_attn_dh(const AttnArgs &a0, hipStream_t st) {
     }
     const int ntq = a.m > 32 ? 3 : (a.m + 15) / 16;
     a.n_rblocks = (a.m + ntq * 16 - 1) / (ntq * 16);
+    a.part_span = ATTN_CHUNK;
+    if (a.rows_live == nullptr && a.slot_const < 0 && a.n_seqs * a.m > 48 && a.m <= ATTN_COMPACT_ROWS) {     // wide batched step
+        a.n_chunks = (a.n_chunks + ATTN_WALK_CHUNKS - 1) / ATTN_WALK_CHUNKS;
+        a.part_span = ATTN_CHUNK * ATTN_WALK_CHUNKS;
+        dim3 wgrid(a.n_chunks, a.H, a.n_seqs * a.n_rblocks);
+        if (ntq == 1) hipLaunchKernelGGL((attn_walk_bf16_kernel<DH, 1, KVS>), wgrid, dim3(256), 0, st, a);
+        else if (ntq == 2) hipLaunchKernelGGL((attn_walk_bf16_kernel<DH, 2, KVS>), wgrid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((attn_walk_bf16_kernel<DH, 3, KVS>), wgrid, dim3(256), 0, st, a);
+        hipLaunchKernelGGL((attn_combine_bf16_kernel<DH>), dim3(a.n_seqs * a.m, a.H), dim3(DH / 4), 0, st, a, a.n_rblocks * ntq * 16);
+        return;
+    }
     dim3 grid(a.n_chunks, a.H, a.n_seqs * a.n_rblocks);
     if (a.rows_live != nullptr) {                      // generation step of one sequence: padding rows known on the device
         if (ntq == 1) hipLaunchKernelGGL((attn_bf16_kernel<DH, 1, KVS, true>), grid, dim3(256), 0, st, a);
