@@ -38,17 +38,32 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def kernel_source_sha():
+    """sha256 of the HIP source that holds the decoding GEMM (the profile summaries record it)."""
+    import hashlib
+    path = os.path.join(ROOT, "paper_2304_04487_amd", "csrc", "kernels_bf16.hip")
+    try:
+        return hashlib.sha256(open(path, "rb").read()).hexdigest()
+    except OSError:
+        return None
+
+
 def measured_traffic():
     """HBM bytes per launch of the gate/up GEMM from the committed rocprofv3 --pmc summary
-    (FETCH_SIZE + WRITE_SIZE, calibrated on a copy of known size); None if not recorded."""
+    (FETCH_SIZE + WRITE_SIZE, calibrated on a copy of known size).  The summary records the sha256 of
+    the kernel source it was measured on; a figure from another version of the source is not reported
+    (None), so it cannot go stale unnoticed."""
     path = os.path.join(ROOT, "profiles", "gemm_gate_up_7b_decode_step_pmc.md")
+    traffic, sha = None, None
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
-                return int(float(line.split(":")[1]))
+                traffic = int(float(line.split(":")[1]))
+            if line.startswith("kernel_source_sha256:"):
+                sha = line.split(":")[1].strip()
     except OSError:
-        pass
-    return None
+        return None
+    return traffic if (sha is not None and sha == kernel_source_sha()) else None
 
 
 def _host_threads():
@@ -260,6 +275,8 @@ def main():
     ap.add_argument("--mb-iters", type=int, default=20, help="microbenchmark: timed steps per case")
     ap.add_argument("--mb-skip-imported", action="store_true")
     ap.add_argument("--mb-skip-computed", action="store_true")
+    ap.add_argument("--profile-prefill", type=int, default=0,
+                    help="profiling aid (for rocprofv3): skip the benchmark, run this many prompt passes of the workload's prompt, print nothing")
     ap.add_argument("--profile-steps", type=int, default=0,
                     help="profiling aid (for rocprofv3): skip the benchmark, run this many k-draft verification steps "
                          "on a random KV cache of prompt length plus one plain 256 MiB device copy, print nothing")
@@ -290,6 +307,13 @@ def main():
     del w
     log(f"[bench] context created in {time.time() - t0:.1f}s, {ctx.device_bytes() / 1e9:.2f} GB on device; {ctx.describe()}")
 
+    if args.profile_prefill:
+        for _ in range(args.profile_prefill):
+            ctx.reset()
+            ctx.prefill(prompt)
+        torch.cuda.synchronize()
+        ctx.close()
+        return
     if args.profile_steps:
         # what one decoding step launches, in isolation, for counter collection: the cache content does
         # not matter for traffic, so it is imported instead of computed; the copy of known size
