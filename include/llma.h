@@ -233,6 +233,14 @@ int llma_get_kernel_timing(llma_ctx *ctx, int64_t *launches, double *total_ms);
  * them.  The activations are whatever the context's scratch holds; outputs go to scratch.
  * bf16 models only.  Synchronises the stream.  For the roofline figure of the benchmark. */
 int llma_time_ffn_gemm(llma_ctx *ctx, int32_t rows, int32_t reps, double *mean_us);
+/* The same measurement for any weight matrix of a layer and any step size the context admits:
+ * which = 0 QKV, 1 attention output, 2 FFN gate/up, 3 FFN down, 4 LM head; rows = 1 ..
+ * max_batch * (max_k + 1).  Launches what a step of that many rows launches for the matrix
+ * (up to 48 rows the decoding GEMM, above that the panel GEMM in its split-K form together
+ * with its finishing kernel).  which = 0 appends K / V rows to sequence slot 0 at position 0
+ * and every call overwrites the context's activation scratch: llma_reset the context before
+ * decoding with it again.  Synchronises the stream. */
+int llma_time_step_gemm(llma_ctx *ctx, int32_t which, int32_t rows, int32_t reps, double *mean_us);
 /* One line of text about what the context tuned at creation (the work division of the decoding
  * GEMMs, which llma_create picks by timing; it changes no result).  buf: HOST, cap bytes. */
 int llma_describe(const llma_ctx *ctx, char *buf, int32_t cap);

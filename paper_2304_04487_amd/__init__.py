@@ -24,7 +24,7 @@ EXPORTS = [
     "llma_create", "llma_destroy", "llma_last_error", "llma_reset", "llma_prefill", "llma_get_state",
     "llma_set_pending", "llma_kv_import", "llma_find_trigger", "llma_verify_step",
     "llma_verify_step_batch", "llma_generate", "llma_generate_batch", "llma_set_logits_dump", "llma_set_option",
-    "llma_get_kernel_timing", "llma_time_ffn_gemm", "llma_device_bytes", "llma_find_trigger_static", "llma_truncate",
+    "llma_get_kernel_timing", "llma_time_ffn_gemm", "llma_time_step_gemm", "llma_device_bytes", "llma_find_trigger_static", "llma_truncate",
     "llma_describe",
 ]
 LLMA_TRIGGER_STATIC_MAX_REF = 1 << 20
@@ -87,6 +87,7 @@ def load_library() -> ctypes.CDLL:
     lib.llma_set_option.argtypes = [vp, c_int32, c_int32]
     lib.llma_get_kernel_timing.argtypes = [vp, POINTER(c_int64), POINTER(c_double)]
     lib.llma_time_ffn_gemm.argtypes = [vp, c_int32, c_int32, POINTER(c_double)]
+    lib.llma_time_step_gemm.argtypes = [vp, c_int32, c_int32, c_int32, POINTER(c_double)]
     lib.llma_describe.argtypes = [vp, c_char_p, c_int32]
     lib.llma_device_bytes.argtypes = [vp]
     lib.llma_device_bytes.restype = c_int64
@@ -291,6 +292,11 @@ class Context:
     def time_ffn_gemm(self, rows: int, reps: int) -> float:
         us = c_double()
         self._ck(self.lib.llma_time_ffn_gemm(self._h, rows, reps, byref(us)))
+        return us.value
+
+    def time_step_gemm(self, which: int, rows: int, reps: int) -> float:
+        us = c_double()
+        self._ck(self.lib.llma_time_step_gemm(self._h, which, rows, reps, byref(us)))
         return us.value
 
     def describe(self) -> str:

@@ -103,6 +103,7 @@ struct GemmArgs {          // bf16 path (fields marked f32 are used by the fp32 
     int ssq_tiles;         //   rstd[row] = rsqrt(sum / (16 ssq_tiles) + eps)
     float eps;
     const float *rstd_in;  // panel GEMM only: [rows] precomputed rstd (instead of ssq_in)
+    float *rstd_out;       // panel GEMM, split-K form: if set, one extra workgroup computes every row's rstd from ssq_in into it (for the finishing kernel)
     const int *rows_live;  // tile-K GEMM only, may be null: device int, rows 0 .. *rows_live carry tokens (the rest of `rows` is padding)
     int panel_rb;          // panel GEMM only: row blocks (set by the launcher)
     int ksplit;            // panel GEMM only: > 1 = the K axis is cut into this many ranges of k-chunks, partial sums via `part`

@@ -15,6 +15,8 @@
 #include <stdlib.h>
 
 #include <atomic>
+#include <type_traits>
+#include <utility>
 
 #include "common.h"
 #include "kernels.h"
@@ -565,7 +567,44 @@ __device__ __forceinline__ void offset_rows(GemmArgs &a, const GemmPlan &p, int 
     if (a.q_hi) { a.q_hi = (bf16_t *)a.q_hi + (size_t)t0 * (a.H * a.dh / 32) * 512; a.q_lo = (bf16_t *)a.q_lo + (size_t)t0 * (a.H * a.dh / 32) * 512; }
 }
 
+// rstd[row] = rsqrt(sum of the row's per-tile sums of squares / d + eps), same summation order as
+// the decoding kernels' in-kernel version (16 threads per row, contiguous chunks, butterfly); r = the
+// calling thread's row (whole waves call this: the butterfly runs over 16-lane groups)
+__device__ __forceinline__ void rstd_of_row(const float *__restrict__ ssq, int ssq_tiles, float eps, float *__restrict__ rstd, int rows, int r, int i) {
+    const int chunk = (ssq_tiles + 15) / 16;
+    const int j0 = i * chunk, j1 = (j0 + chunk < ssq_tiles) ? j0 + chunk : ssq_tiles;
+    float ss = 0.f;
+    if (r < rows) {
+        const float *sp = ssq + (size_t)r * ssq_tiles;
+        for (int j = j0; j < j1; j += 16) {
+            float v[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u)
+                if (j + u < j1) v[u] = sp[j + u];
+#pragma unroll
+            for (int u = 0; u < 16; ++u)
+                if (j + u < j1) ss += v[u];
+        }
+    }
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) ss += __shfl_xor(ss, off);
+    if (i == 0 && r < rows) rstd[r] = 1.0f / sqrtf(ss / (float)(ssq_tiles * 16) + eps);
+}
+
+// calls f(integral_constant<int, 0>), f(..1), ... in order until one returns false
+template <class F, int... I>
+__device__ __forceinline__ void chunks_in_order(std::integer_sequence<int, I...>, F &&f) {
+    bool go = true;
+    ((go = go && f(std::integral_constant<int, I>{})), ...);
+}
+
 #define PANEL_KC 2          // k-steps per LDS chunk
+#ifndef PN_TRACE
+#define PN_TRACE(slot, chunk)   // (timeline probe of the one-off microbenchmarks; nothing in the library build)
+#endif
+#ifndef PANEL_WD
+#define PANEL_WD 8          // k-steps of weights in registers (one in use, the others in flight)
+#endif
 // (four or more weight tiles per wave: accumulators for up to 9 row tiles each need the whole register
 //  file of a SIMD lane, 512 registers, i.e. one wave per SIMD; otherwise two)
 template <int RT, int EPI, int FT, int WV>
@@ -580,6 +619,14 @@ __global__ __launch_bounds__(WV * 64, (FT * (EPI == EPI_SWIGLU ? 2 : 1) >= 4 ? 1
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const GemmPlan &p = a0.plan;
     const int KSp = p.KSp;
+    if (a0.rstd_out != nullptr && blockIdx.x == gridDim.x - 1) {
+        // split-K form: one workgroup more than the tiles need turns the rows' sums of squares into
+        // rstd for the finishing kernel, beside the others instead of in a launch of its own
+        if (blockIdx.y == 0)
+            for (int r = threadIdx.x >> 4; r < ((a0.rows + 15) & ~15); r += NTHR / 16)
+                rstd_of_row(a0.ssq_in, a0.ssq_tiles, a0.eps, a0.rstd_out, a0.rows, r, threadIdx.x & 15);
+        return;
+    }
     // Workgroup order: the row blocks of one feature block get ids that differ by multiples of 8, i.e.
     // they are dispatched close together and onto the same XCD, so the feature block's weights are
     // fetched from HBM once and found in that XCD's L2 by the other row blocks.
@@ -634,16 +681,13 @@ __global__ __launch_bounds__(WV * 64, (FT * (EPI == EPI_SWIGLU ? 2 : 1) >= 4 ? 1
             if (q < 2 * RT * KC) xs[(buf * 2 * RT * KC + q) * 64 + lane] = v[j];
         }
     };
-    // weights of chunk kc; a k-step past the end of K (ragged last chunk) gets zeros and adds nothing
-    auto fetch_w = [&](int kc, u32x4 (&av)[AT][KC]) {
+    // weights of k-step k0, one 1 KiB block per tile; a k-step past the end of K (ragged last chunk)
+    // gets zeros and adds nothing
+    auto fetch_w = [&](int k0, u32x4 (&av)[AT]) {
+        const int k = k0 < KSp ? k0 : KSp - 1;
+        const unsigned keep = k0 < KSp ? 0xffffffffu : 0u;          // (a mask, not a select: the load stays unconditional)
 #pragma unroll
-        for (int u = 0; u < KC; ++u) {
-            const int k0 = kc * KC + u;
-            const int k = k0 < KSp ? k0 : KSp - 1;
-            const unsigned keep = k0 < KSp ? 0xffffffffu : 0u;      // (a mask, not a select: the load stays unconditional)
-#pragma unroll
-            for (int i = 0; i < AT; ++i) av[i][u] = *(const u32x4 *)(wb[i] + (size_t)k * 1024 + w_lane) & keep;
-        }
+        for (int i = 0; i < AT; ++i) av[i] = *(const u32x4 *)(wb[i] + (size_t)k * 1024 + w_lane) & keep;
     };
 
     f32x4 acc[AT][RT];
@@ -658,45 +702,69 @@ __global__ __launch_bounds__(WV * 64, (FT * (EPI == EPI_SWIGLU ? 2 : 1) >= 4 ? 1
     const int n_split = a0.ksplit > 1 ? a0.ksplit : 1;
     const int NC_all = (KSp + KC - 1) / KC;
     const int kc_lo = (int)((long)NC_all * blockIdx.y / n_split), NC = (int)((long)NC_all * (blockIdx.y + 1) / n_split);
-    u32x4 xvA[PER], xvB[PER], avA[AT][KC], avB[AT][KC];
+    // The weights come straight from HBM, whose latency under load (2 us and more) is several chunks
+    // of MFMA work, so they are requested WD - 1 k-steps ahead into a ring of WD register sets; the loop
+    // below is unrolled over one turn of the ring (WD / KC chunks), which gives every set and both
+    // activation staging arrays one fixed role per call site.
+    // The weights come straight from HBM, whose latency under load (2 us and more) is several chunks
+    // of MFMA work, so they are requested WD - 1 k-steps ahead into a ring of WD register sets; the loop
+    // below is unrolled over one turn of the ring (WD / KC chunks), which gives every set and both
+    // activation staging arrays one fixed role per call site (one body taking either role made the
+    // compiler copy registers between the roles every chunk, behind a wait for all loads in flight).
+    // A wave's loads complete in the order it issued them, so an activation block (an L2 hit) waits
+    // behind every weight block requested before it: the activations are requested two chunks before
+    // they are parked in LDS.
+    constexpr int WD = PANEL_WD;
+    static_assert(WD % (2 * KC) == 0, "one turn of the weight ring is a whole number of LDS buffer pairs");
+    u32x4 xvA[PER], xvB[PER], wr[WD][AT];
+    PN_TRACE(0, 63);
     fetch_x(kc_lo, xvA);
-    fetch_w(kc_lo, avA);
-    fetch_x(kc_lo + 1 < NC ? kc_lo + 1 : kc_lo, xvB);
-    if (EPI != EPI_RESID)
+#pragma unroll
+    for (int j = 0; j < WD - 1; ++j) fetch_w(kc_lo * KC + j, wr[j]);
+    fetch_x(kc_lo + 1, xvB);
+    if (EPI != EPI_RESID && n_split == 1)
         for (int r = threadIdx.x; r < 16 * RT; r += NTHR) rstd_s[r] = (r < a.rows) ? a.rstd_in[r0 + r] : 0.f;
     stash_x(0, xvA);
     __syncthreads();
-    // One chunk: request operands (the weights of the next chunk, the activations of the chunk after
-    // it: they still have to pass through LDS), run this chunk's MFMAs out of LDS buffer `buf` and
-    // weight registers `av`, park the next chunk's activations (requested a chunk ago, `x_park`) in
-    // the other LDS buffer.  The loop below calls it twice per round with the buffers swapped, so
-    // that every register array has one fixed role per call site (one body taking either buffer made
-    // the compiler copy accumulators and weight registers between the two roles every chunk, behind
-    // a wait for all loads in flight).
-    auto chunk = [&](int kc, int buf, u32x4 (&av)[AT][KC], u32x4 (&avn)[AT][KC], u32x4 (&x_park)[PER], u32x4 (&x_req)[PER]) {
-        fetch_x(kc + 2 < NC ? kc + 2 : kc, x_req);     // (x_req held this chunk's activations, in LDS since the last barrier;
-        fetch_w(kc + 1 < NC ? kc + 1 : kc, avn);       //  the last chunks request themselves again, unused)
+    PN_TRACE(1, 63);
+    // One chunk: request operands (the weights WD - 1 k-steps ahead, the activations of the chunk after
+    // the next: they still have to pass through LDS), run this chunk's MFMAs out of LDS buffer c & 1
+    // and the ring, park the next chunk's activations (requested a chunk ago) in the other LDS buffer,
+    // which was last read before the previous barrier.  (Requests past the end of the range or of K
+    // are clamped, unused.)
+    auto chunk = [&](int kc0, auto slot) -> bool {
+        constexpr int c = decltype(slot)::value;        // chunk within the turn of the ring
+        constexpr int buf = c & 1;
+        const int kc = kc0 + c;
+        if (kc >= NC) return false;
+        PN_TRACE(0, kc - kc_lo);
+        u32x4 (&x_park)[PER] = buf ? xvA : xvB;
+        u32x4 (&x_req)[PER] = buf ? xvB : xvA;          // held this chunk's activations, in LDS since the last barrier
+        fetch_x(kc + 2, x_req);
 #pragma unroll
         for (int u = 0; u < KC; ++u) {
+            const int j = c * KC + u;                   // ring set of this k-step (a constant after unrolling)
+            fetch_w(kc * KC + u + WD - 1, wr[(j + WD - 1) % WD]);   // into the set the previous k-step used
 #pragma unroll
             for (int t = 0; t < RT; ++t) {
                 const u32x4 bh = xs[buf * 2 * CH + (t * KC + u) * 64 + lane];
                 const u32x4 bl = xs[buf * 2 * CH + CH + (t * KC + u) * 64 + lane];
 #pragma unroll
                 for (int i = 0; i < AT; ++i) {
-                    acc[i][t] = mfma16x16x32(av[i][u], bh, acc[i][t]);
-                    acc[i][t] = mfma16x16x32(av[i][u], bl, acc[i][t]);
+                    acc[i][t] = mfma16x16x32(wr[j][i], bh, acc[i][t]);
+                    acc[i][t] = mfma16x16x32(wr[j][i], bl, acc[i][t]);
                 }
             }
         }
-        stash_x(buf ^ 1, x_park);                      // the other buffer was last read before the previous barrier
+        PN_TRACE(1, kc - kc_lo);
+        stash_x(buf ^ 1, x_park);
+        PN_TRACE(2, kc - kc_lo);
         __syncthreads();
+        PN_TRACE(3, kc - kc_lo);
+        return true;
     };
-    for (int kc = kc_lo; kc < NC; kc += 2) {
-        chunk(kc, 0, avA, avB, xvB, xvA);
-        if (kc + 1 >= NC) break;
-        chunk(kc + 1, 1, avB, avA, xvA, xvB);
-    }
+    for (int kc = kc_lo; kc < NC; kc += WD / KC)
+        chunks_in_order(std::make_integer_sequence<int, WD / KC>{}, [&](auto slot) { return chunk(kc, slot); });
 
     if (n_split > 1) {
         // partial sums as register images: [range][tile (SwiGLU: gate tiles, then up tiles)][row tile][lane]
@@ -709,6 +777,7 @@ __global__ __launch_bounds__(WV * 64, (FT * (EPI == EPI_SWIGLU ? 2 : 1) >= 4 ? 1
                 for (int t = 0; t < RT; ++t)
                     if (task0 + f < p.tasks && rt0 + t < n_rt_total)
                         part[(((size_t)blockIdx.y * (p.tasks * TILES) + task0 + f + i * p.tasks) * n_rt_total + rt0 + t) * 64 + lane] = acc[f * TILES + i][t];
+        PN_TRACE(2, 63);
         return;
     }
     // ---- epilogues, one feature tile (pair) at a time
@@ -728,28 +797,8 @@ __global__ __launch_bounds__(WV * 64, (FT * (EPI == EPI_SWIGLU ? 2 : 1) >= 4 ? 1
     }
 }
 
-// rstd[row] = rsqrt(sum of the row's per-tile sums of squares / d + eps), same summation order as
-// the decoding kernels' in-kernel version (16 threads per row, contiguous chunks, butterfly)
 __global__ __launch_bounds__(256) void rstd_rows_kernel(const float *__restrict__ ssq, int ssq_tiles, float eps, float *__restrict__ rstd, int rows) {
-    const int r = blockIdx.x * 16 + (threadIdx.x >> 4), i = threadIdx.x & 15;
-    const int chunk = (ssq_tiles + 15) / 16;
-    const int j0 = i * chunk, j1 = (j0 + chunk < ssq_tiles) ? j0 + chunk : ssq_tiles;
-    float ss = 0.f;
-    if (r < rows) {
-        const float *sp = ssq + (size_t)r * ssq_tiles;
-        for (int j = j0; j < j1; j += 16) {
-            float v[16];
-#pragma unroll
-            for (int u = 0; u < 16; ++u)
-                if (j + u < j1) v[u] = sp[j + u];
-#pragma unroll
-            for (int u = 0; u < 16; ++u)
-                if (j + u < j1) ss += v[u];
-        }
-    }
-#pragma unroll
-    for (int off = 1; off < 16; off <<= 1) ss += __shfl_xor(ss, off);
-    if (i == 0 && r < rows) rstd[r] = 1.0f / sqrtf(ss / (float)(ssq_tiles * 16) + eps);
+    rstd_of_row(ssq, ssq_tiles, eps, rstd, rows, blockIdx.x * 16 + (threadIdx.x >> 4), threadIdx.x & 15);
 }
 void launch_rstd_rows(const float *ssq, int ssq_tiles, float eps, float *rstd, int rows, hipStream_t st) {
     hipLaunchKernelGGL(rstd_rows_kernel, dim3((rows + 15) / 16), dim3(256), 0, st, ssq, ssq_tiles, eps, rstd, rows);
@@ -796,7 +845,8 @@ static void launch_panel_cfg(const GemmArgs &a, hipStream_t st) {
     const int FB = ((p.tasks + WV * FT - 1) / (WV * FT) + 7) / 8 * 8;    // feature blocks, padded to whole groups of 8
     GemmArgs a2 = a;
     a2.panel_rb = (a.rows + 16 * RT - 1) / (16 * RT);
-    dim3 grid(FB * a2.panel_rb, a.ksplit > 1 ? a.ksplit : 1), block(WV * 64);
+    if (a.ksplit <= 1) a2.rstd_out = nullptr;
+    dim3 grid(FB * a2.panel_rb + (a2.rstd_out ? 1 : 0), a.ksplit > 1 ? a.ksplit : 1), block(WV * 64);
     static std::atomic<uint64_t> done{0};
     allow_full_lds((const void *)gemm_panel_bf16<RT, EPI, FT, WV>, done);
     hipLaunchKernelGGL((gemm_panel_bf16<RT, EPI, FT, WV>), grid, block, lds, st, a2);

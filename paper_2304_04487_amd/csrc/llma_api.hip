@@ -521,6 +521,13 @@ static int forward_bf16(llma_ctx *c, int n_seqs, int m, int n_chunks, bool lm_he
         if (lm_head && ga.plan.n_split > 1) { ga.ksplit = ga.plan.n_split; ga.part = c->part; }
         launch_gemm_panel_bf16(ga, st);
     };
+    // panel GEMM whose epilogue scales by the rows' rstd: the split-K form computes it in an extra
+    // workgroup of its first kernel (its finishing kernel is the reader), otherwise a launch of its own
+    auto panel_norm_gemm = [&](GemmArgs &ga) {
+        if (lm_head && ga.plan.n_split > 1) ga.rstd_out = c->rstd;
+        else launch_rstd_rows(c->ssq, d / 16, g.rms_eps, c->rstd, R, st);
+        panel_gemm(ga);
+    };
     base.rstd_in = c->rstd;
     base.ssq_tiles = d / 16; base.H = H; base.dh = dh; base.max_seq = c->seq_cap; base.nx_KSp = ksp_d;
     AttnArgs aa{};
@@ -534,7 +541,7 @@ static int forward_bf16(llma_ctx *c, int n_seqs, int m, int n_chunks, bool lm_he
         ga.W = c->wqkv[l]; ga.plan = c->plan_qkv; ga.Xhi = c->xhi; ga.Xlo = c->xlo; ga.epi = EPI_QKV; ga.ssq_in = c->ssq;
         ga.row_pos = c->s.row_pos; ga.row_slot = c->s.row_slot; ga.row_cs = c->s.row_cs; ga.q_hi = c->q; ga.q_lo = c->q_lo;
         ga.k_hi = c->kc[l]; ga.k_lo = c->kc_lo[l]; ga.v_hi = c->vc[l]; ga.v_lo = c->vc_lo[l];
-        if (panel) { launch_rstd_rows(c->ssq, d / 16, g.rms_eps, c->rstd, R, st); panel_gemm(ga); }
+        if (panel) panel_norm_gemm(ga);
         else tilek_gemm(ga);
         aa.Khi = c->kc[l]; aa.Klo = c->kc_lo[l]; aa.Vhi = c->vc[l]; aa.Vlo = c->vc_lo[l];
         launch_attn_bf16(aa, st);
@@ -546,8 +553,7 @@ static int forward_bf16(llma_ctx *c, int n_seqs, int m, int n_chunks, bool lm_he
         ga.W = c->wgu[l]; ga.plan = c->plan_gu; ga.Xhi = c->xhi; ga.Xlo = c->xlo; ga.epi = EPI_SWIGLU; ga.ssq_in = c->ssq;
         ga.act_hi = c->act_hi; ga.act_lo = c->act_lo; ga.act_KSp = c->plan_down.KSp;
         if (panel) {
-            launch_rstd_rows(c->ssq, d / 16, g.rms_eps, c->rstd, R, st);
-            panel_gemm(ga);
+            panel_norm_gemm(ga);
         } else if (c->opt_timing) {
             EventPair ep;
             HIP_TRY(c, hipEventCreate(&ep.a));
@@ -568,7 +574,7 @@ static int forward_bf16(llma_ctx *c, int n_seqs, int m, int n_chunks, bool lm_he
         GemmArgs ga = base;
         ga.W = c->lm_head; ga.plan = c->plan_lm; ga.Xhi = c->xhi; ga.Xlo = c->xlo; ga.epi = EPI_LMHEAD; ga.ssq_in = c->ssq;
         ga.out = c->logits_dump; ga.pval = c->pval; ga.pidx = c->pidx; ga.n_part = c->n_part;
-        if (panel) { launch_rstd_rows(c->ssq, d / 16, g.rms_eps, c->rstd, R, st); panel_gemm(ga); }
+        if (panel) panel_norm_gemm(ga);
         else tilek_gemm(ga);
     }
     if (refused) return fail(c, LLMA_E_INVAL, "forward: a step of %d rows reached the decoding-step GEMM (1..48 rows)", R);
@@ -1060,23 +1066,33 @@ extern "C" int llma_set_option(llma_ctx *c, int32_t option, int32_t value) {
     }
 }
 
-extern "C" int llma_time_ffn_gemm(llma_ctx *c, int32_t rows, int32_t reps, double *mean_us) {
-    if (!c || !mean_us) return fail(c, LLMA_E_INVAL, "llma_time_ffn_gemm: null argument");
-    if (c->cfg.dtype != LLMA_DTYPE_BF16) return fail(c, LLMA_E_INVAL, "llma_time_ffn_gemm: bf16 models only");
-    if (rows < 1 || rows > 48 || rows > c->cfg.max_batch * (c->cfg.max_k + 1) || reps < 1 || reps > 100000)
-        return fail(c, LLMA_E_RANGE, "llma_time_ffn_gemm: rows %d (1..min(48, max_batch (max_k + 1))) or reps %d (1..100000) out of range", rows, reps);
+extern "C" int llma_time_step_gemm(llma_ctx *c, int32_t which, int32_t rows, int32_t reps, double *mean_us) {
+    if (!c || !mean_us) return fail(c, LLMA_E_INVAL, "llma_time_step_gemm: null argument");
+    if (c->cfg.dtype != LLMA_DTYPE_BF16) return fail(c, LLMA_E_INVAL, "llma_time_step_gemm: bf16 models only");
+    if (which < 0 || which > 4) return fail(c, LLMA_E_RANGE, "llma_time_step_gemm: matrix %d (0 QKV, 1 O, 2 gate/up, 3 down, 4 LM head)", which);
+    if (rows < 1 || rows > c->cfg.max_batch * (c->cfg.max_k + 1) || reps < 1 || reps > 100000)
+        return fail(c, LLMA_E_RANGE, "llma_time_step_gemm: rows %d (1..max_batch (max_k + 1) = %d) or reps %d (1..100000) out of range",
+                    rows, c->cfg.max_batch * (c->cfg.max_k + 1), reps);
     const llma_model_cfg &g = c->cfg;
-    GemmArgs ga = step_gemm_args(c, 2, 0, rows);
+    HIP_TRY(c, hipStreamSynchronize(c->st));
+    if (which == 0) {           // the QKV epilogue appends K and V at (row_slot, row_pos): slot 0, position 0 for every row
+        HIP_TRY(c, hipMemsetAsync(c->s.row_pos, 0, sizeof(int32_t) * rows, c->st));
+        HIP_TRY(c, hipMemsetAsync(c->s.row_slot, 0, sizeof(int32_t) * rows, c->st));
+    }
     hipEvent_t e0, e1;
     HIP_TRY(c, hipEventCreate(&e0));
     HIP_TRY(c, hipEventCreate(&e1));
-    HIP_TRY(c, hipStreamSynchronize(c->st));
     for (int pass = 0; pass < 2; ++pass) {              // pass 0 warms up (first-launch set-up of the kernel)
         const int n = pass ? reps : (reps < g.n_layers ? reps : g.n_layers);
         HIP_TRY(c, hipEventRecord(e0, c->st));
         for (int r = 0; r < n; ++r) {
-            ga.W = c->wgu[r % g.n_layers];
-            if (!launch_gemm_bf16(ga, c->st)) return fail(c, LLMA_E_RANGE, "llma_time_ffn_gemm: rows %d outside 1..48", rows);
+            GemmArgs ga = step_gemm_args(c, which, r % g.n_layers, rows);
+            if (rows > 48) {                            // the step's own choice: panel kernel, split-K form
+                if (ga.plan.n_split > 1) { ga.ksplit = ga.plan.n_split; ga.part = c->part; if (ga.epi != EPI_RESID) ga.rstd_out = c->rstd; }
+                launch_gemm_panel_bf16(ga, c->st);
+            } else if (!launch_gemm_bf16(ga, c->st)) {
+                return fail(c, LLMA_E_RANGE, "llma_time_step_gemm: launch refused for %d rows", rows);
+            }
         }
         HIP_TRY(c, hipEventRecord(e1, c->st));
         HIP_TRY(c, hipEventSynchronize(e1));
@@ -1088,6 +1104,11 @@ extern "C" int llma_time_ffn_gemm(llma_ctx *c, int32_t rows, int32_t reps, doubl
     (void)hipEventDestroy(e1);
     *mean_us = (double)ms * 1e3 / reps;
     return LLMA_OK;
+}
+
+extern "C" int llma_time_ffn_gemm(llma_ctx *c, int32_t rows, int32_t reps, double *mean_us) {
+    if (rows > 48) return fail(c, LLMA_E_RANGE, "llma_time_ffn_gemm: rows %d outside 1..48", rows);
+    return llma_time_step_gemm(c, 2, rows, reps, mean_us);
 }
 
 extern "C" int llma_get_kernel_timing(llma_ctx *c, int64_t *launches, double *total_ms) {

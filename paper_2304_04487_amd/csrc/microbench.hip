@@ -20,8 +20,14 @@ __device__ unsigned long long tk_trace[TR_WG * 16 * 4];
 #define TK_TRACE_1 if ((threadIdx.x & 63) == 0 && !tk_seen) { tk_seen = 1; TK_STAMP(1); }
 #define TK_TRACE_2 if ((threadIdx.x & 63) == 0) TK_STAMP(2)
 #define TK_TRACE_3 if ((threadIdx.x & 63) == 0) TK_STAMP(3)
+// panel GEMM (batched steps): per wave and chunk of the K loop: 0 chunk start, 1 MFMAs issued, 2 next chunk's
+// activations parked in LDS, 3 past the chunk barrier; chunk 63: 0 kernel entry, 1 first chunk staged, 2 partial sums written
+#define PN_WG 1024
+__device__ unsigned long long pn_trace[(size_t)PN_WG * 8 * 64 * 4];
 #ifdef MICROBENCH_TIMELINE
 #define TK_TRACE(slot) TK_TRACE_##slot
+#define PN_TRACE(slot, chunk) if ((threadIdx.x & 63) == 0 && (chunk) < 64 && blockIdx.y * gridDim.x + blockIdx.x < PN_WG) \
+    pn_trace[(((size_t)(blockIdx.y * gridDim.x + blockIdx.x) * 8 + (threadIdx.x >> 6)) * 64 + (chunk)) * 4 + (slot)] = wall_clock64()
 #endif
 #include "kernels_bf16.hip"
 
@@ -55,9 +61,9 @@ static void *zalloc(size_t b) { void *p; CK(hipMalloc(&p, b)); CK(hipMemset(p, 0
 static Bufs make_bufs() {
     Bufs b;
     b.xh = zalloc(4 << 20); b.xl = zalloc(4 << 20); b.qh = zalloc(4 << 20); b.ql = zalloc(4 << 20); b.acth = zalloc(8 << 20); b.actl = zalloc(8 << 20);
-    b.h = (float *)zalloc(64 * D * 4); b.ssq = (float *)zalloc(64 * 256 * 4); b.gain = (float *)zalloc(D * 4);
+    b.h = (float *)zalloc(512 * D * 4); b.ssq = (float *)zalloc(512 * 256 * 4); b.gain = (float *)zalloc(D * 4);
     b.pval = (float *)zalloc(64 * 2000 * 4); b.pidx = (int *)zalloc(64 * 2000 * 4); b.sink = (unsigned *)zalloc(64);
-    b.rpos = (int *)zalloc(256); b.rslot = (int *)zalloc(256); b.cs = (float *)zalloc((size_t)MAX_SEQ * 64 * 2 * 4);
+    b.rpos = (int *)zalloc(4096); b.rslot = (int *)zalloc(4096); b.cs = (float *)zalloc((size_t)MAX_SEQ * 64 * 2 * 4);
     const size_t kv = (size_t)H * MAX_SEQ * DH * 2;
     b.kh = zalloc(kv); b.kl = zalloc(kv); b.vh = zalloc(kv); b.vl = zalloc(kv);
     return b;
@@ -144,6 +150,59 @@ static void timeline_one(const Shape &sh, const Bufs &b, int rows, int waves) {
         for (int g = 0; g < G; ++g) for (int w = 0; w < (sl == 3 ? 1 : waves); ++w) v.push_back((at(g, w, sl) - t0) * 0.01);
         std::sort(v.begin(), v.end()); const size_t n = v.size();
         printf("   %-15s min %6.2f  p10 %6.2f  p50 %6.2f  p90 %6.2f  max %6.2f us\n", nm[sl], v[0], v[n / 10], v[n / 2], v[n * 9 / 10], v[n - 1]);
+    }
+}
+// one split-K launch of the panel GEMM with `rows` rows: where the time of a workgroup goes
+static void timeline_panel(const Shape &sh, const Bufs &b, int rows, float *part, float *rstd) {
+    size_t bytes; GemmArgs a = make_args(sh, b, rows, bytes);
+    a.ksplit = a.plan.n_split; a.part = part; a.rstd_in = rstd;
+    const size_t stride = (bytes + (8 << 20)) & ~(size_t)4095;
+    for (int r = 0; r < 3; ++r) { a.W = wbuf + (size_t)r * stride; launch_gemm_panel_bf16(a, 0); }
+    CK(hipDeviceSynchronize());
+    std::vector<unsigned long long> t((size_t)PN_WG * 8 * 64 * 4, 0);
+    CK(hipMemcpyToSymbol(HIP_SYMBOL(pn_trace), t.data(), t.size() * 8));
+    a.W = wbuf + (size_t)3 * stride;
+    CK(hipEventRecord(e0, 0)); launch_gemm_panel_bf16(a, 0); CK(hipEventRecord(e1, 0)); CK(hipEventSynchronize(e1)); CK(hipGetLastError());
+    float ms; CK(hipEventElapsedTime(&ms, e0, e1));
+    CK(hipMemcpyFromSymbol(t.data(), HIP_SYMBOL(pn_trace), t.size() * 8));
+    auto at = [&](int g, int w, int ch, int sl) { return t[(((size_t)g * 8 + w) * 64 + ch) * 4 + sl]; };
+    unsigned long long t0 = ~0ull;
+    int G = 0;
+    for (int g = 0; g < PN_WG; ++g) if (at(g, 0, 63, 0)) { G = g + 1; t0 = std::min(t0, at(g, 0, 63, 0)); }
+    printf("%s, %d rows, %d K ranges: %d workgroups traced, event pair around panel + finishing kernel %.2f us\n", sh.name, rows, a.ksplit, G, ms * 1e3);
+    std::vector<double> entry, staged, done, mf, park, bar, nch;
+    for (int g = 0; g < G; ++g)
+        for (int w = 0; w < 8; ++w) {
+            entry.push_back((at(g, w, 63, 0) - t0) * 0.01); staged.push_back((at(g, w, 63, 1) - at(g, w, 63, 0)) * 0.01);
+            done.push_back((at(g, w, 63, 2) - t0) * 0.01);
+            int n = 0;
+            for (int ch = 0; ch < 63 && at(g, w, ch, 3); ++ch, ++n) {
+                mf.push_back((at(g, w, ch, 1) - at(g, w, ch, 0)) * 0.01); park.push_back((at(g, w, ch, 2) - at(g, w, ch, 1)) * 0.01);
+                bar.push_back((at(g, w, ch, 3) - at(g, w, ch, 2)) * 0.01);
+            }
+            nch.push_back(n);
+        }
+    auto show = [&](const char *nm, std::vector<double> &v) {
+        std::sort(v.begin(), v.end()); const size_t n = v.size(); double sum = 0; for (double x : v) sum += x;
+        printf("   %-34s mean %6.2f  min %6.2f  p10 %6.2f  p50 %6.2f  p90 %6.2f  max %6.2f us\n", nm, sum / n, v[0], v[n / 10], v[n / 2], v[n * 9 / 10], v[n - 1]);
+    };
+    show("wave entry (after first entry)", entry); show("entry -> first chunk staged", staged); show("chunks per wave", nch);
+    show("chunk: start -> MFMAs issued", mf); show("chunk: park next activations", park); show("chunk: barrier", bar);
+    show("partial sums written (after first entry)", done);
+    // one wave in detail
+    printf("   workgroup 0, wave 0, per chunk (start since entry | MFMAs | park | barrier):");
+    for (int ch = 0; ch < 63 && at(0, 0, ch, 3); ++ch)
+        printf("%s %5.2f|%4.2f|%4.2f|%4.2f", ch % 4 == 0 ? "\n     " : "  ", (at(0, 0, ch, 0) - at(0, 0, 63, 0)) * 0.01, (at(0, 0, ch, 1) - at(0, 0, ch, 0)) * 0.01,
+               (at(0, 0, ch, 2) - at(0, 0, ch, 1)) * 0.01, (at(0, 0, ch, 3) - at(0, 0, ch, 2)) * 0.01);
+    printf("\n");
+}
+static void cmd_panel() {
+    Bufs b = make_bufs();
+    float *part = (float *)zalloc((size_t)64 << 20), *rstd = (float *)zalloc(4096);
+    for (int rows : {144, 272}) {
+        timeline_panel(SHAPES[2], b, rows, part, rstd);
+        timeline_panel(SHAPES[3], b, rows, part, rstd);
+        timeline_panel(SHAPES[0], b, rows, part, rstd);
     }
 }
 static void cmd_timeline() {
@@ -304,7 +363,8 @@ int main(int argc, char **argv) {
     CK(hipMalloc(&wbuf, W_BYTES)); CK(hipMemset(wbuf, 0x11, W_BYTES));
     CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
 #ifdef MICROBENCH_TIMELINE
-    cmd_timeline();
+    if (argc > 1 && !strcmp(argv[1], "panel")) cmd_panel();
+    else cmd_timeline();
 #else
     const char *cmd = argc > 1 ? argv[1] : "";
     if (!strcmp(cmd, "shapes")) cmd_shapes();
