@@ -853,15 +853,15 @@ static void launch_panel_cfg(const GemmArgs &a, hipStream_t st) {
 }
 
 // prompt-processing GEMM over any number of rows (needs a.rstd_in for the norm-scaled epilogues).
-// A workgroup owns WV waves x FT feature tiles (FT = 2; SwiGLU: one gate/up pair) and RT row tiles.
-// Prompt passes: WV = 4, RT = 5..8, two workgroups per compute unit (their chunk barriers fall at
-// different times, which keeps the MFMA pipe busier than one workgroup of 8 waves did); batched steps
-// (split-K): WV = 8, RT = 5..9, one workgroup per compute unit.  A launch runs in rounds of that many
-// workgroups; a round costs about RT + 3 (the weight stream and chunk barriers of a workgroup do not
-// shrink with its height), and the height with the least rounds x (RT + 3) wins: 1535 prompt rows: 6
-// (QKV 3.0 rounds instead of 2.25, O / down exactly 1.0); 144 rows of a batched step: 9 for QKV and
-// gate/up (one row block, the weights pass once: 64 -> 51 us, 104 -> 82 us), 5 for O and down (two row
-// blocks fill the 256 compute units, one would leave half of them idle: 28 vs 33 us, 47 vs 58 us).
+// A workgroup owns WV = 8 waves x FT feature tiles (FT = 2; SwiGLU: one gate/up pair) and RT = 5..9 row
+// tiles, one workgroup per compute unit (two workgroups of 4 waves, whose chunk barriers fall at
+// different times, were 8 % slower on the 1535-row prompt pass once the weights were requested a ring
+// ahead: 46.7 vs 43.0 ms).  A launch runs in rounds of that many workgroups; a round costs about RT + 3
+// (the weight stream and chunk barriers of a workgroup do not shrink with its height), and the height
+// with the least rounds x (RT + 3) wins: 1535 prompt rows: 6 for QKV, O and down, 9 for gate/up; 144
+// rows of a batched step: 9 for QKV and gate/up (one row block, the weights pass once: 64 -> 51 us,
+// 104 -> 82 us), 5 for O and down (two row blocks fill the 256 compute units, one would leave half of
+// them idle: 28 vs 33 us, 47 vs 58 us).
 template <int EPI, int FT, int WV>
 static void launch_panel_wv(const GemmArgs &a, hipStream_t st) {
     static int n_cu = 0;
@@ -892,13 +892,9 @@ static void launch_panel_wv(const GemmArgs &a, hipStream_t st) {
     }
     if (a.ksplit > 1) launch_splitk_finish<EPI>(a, st);
 }
-// prompt passes: two 4-wave workgroups per compute unit (128-feature blocks); split-K steps: one
-// 8-wave workgroup (256-feature blocks), because with a few hundred rows and 2..8 K ranges the
-// activation rows every feature block stages are the larger part of the L2 traffic
 template <int EPI, int FT>
 static void launch_panel_epi(const GemmArgs &a, hipStream_t st) {
-    if (a.ksplit > 1) launch_panel_wv<EPI, FT, 8>(a, st);
-    else launch_panel_wv<EPI, FT, 4>(a, st);
+    launch_panel_wv<EPI, FT, 8>(a, st);
 }
 void launch_gemm_panel_bf16(const GemmArgs &a, hipStream_t st) {
     switch (a.epi) {
@@ -1374,6 +1370,197 @@ __global__ __launch_bounds__(256, 2) void attn_walk_bf16_kernel(AttnArgs a) {
     }
 }
 
+// The same walk for one or two row tiles with the running state per WAVE: a wave folds its 32 positions
+// of every chunk into its own (max, sum, O) in registers -- no LDS and no barrier inside the walk, so
+// the eight waves of a compute unit drift apart and one wave's arithmetic hides the other's loads --
+// and the four waves are merged once, in wave order, at the end of the walk.  A row's result is
+// again a function of absolute positions only (wave w: positions 32 w .. 32 w + 31 of each chunk of
+// the walk in chunk order; then the waves in order; then the walks in order in the combine kernel).
+template <int DH, int NTQ, bool KVS>
+__global__ __launch_bounds__(256, (NTQ == 1 ? 4 : 2)) void attn_walk_wave_bf16_kernel(AttnArgs a) {
+    constexpr int KSTEPS = DH / 32, DT = DH / 16;
+    constexpr int RQ = NTQ * 16;
+    constexpr int OWN = (RQ * (DH / 4) + 255) / 256;                  // merged output elements (float4) per thread
+    __shared__ float sm[4][RQ], sl[4][RQ];
+    __shared__ float so[4][RQ][DH + 4];
+    const int h = blockIdx.y, b = blockIdx.z / a.n_rblocks, rb = blockIdx.z % a.n_rblocks;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 15, g = lane >> 4;
+    const int slot = a.batch_slots[b];
+    const int T = a.T[slot];
+    const int lo_from = (KVS && a.lo_from != nullptr) ? a.lo_from[slot] : 0;
+    const int m = a.m, j0 = rb * RQ;
+    if (j0 >= m) return;
+    const int m_blk = (m - j0 < RQ) ? m - j0 : RQ;
+    const int kv_len = T + j0 + m_blk;                               // positions the block's last row can see
+    const int c0 = blockIdx.x * ATTN_WALK_CHUNKS;
+    if (c0 * ATTN_CHUNK >= kv_len) return;                           // uniform for the workgroup
+    const int c_need = (kv_len + ATTN_CHUNK - 1) / ATTN_CHUNK;
+    const int c1 = c0 + ATTN_WALK_CHUNKS < c_need ? c0 + ATTN_WALK_CHUNKS : c_need;
+    int c_lo = KVS ? lo_from / ATTN_CHUNK : c1;                      // chunks below c_lo: imported bf16 cache, single plane
+    c_lo = c_lo < c0 ? c0 : (c_lo > c1 ? c1 : c_lo);
+    const int d_model = a.H * DH;
+    const size_t head_base = ((size_t)slot * a.H + h) * (size_t)a.max_seq * DH;
+    const bf16_t *kh = (const bf16_t *)a.Khi + head_base, *kl = (const bf16_t *)a.Klo + head_base;
+    const bf16_t *vh = (const bf16_t *)a.Vhi + head_base, *vl = (const bf16_t *)a.Vlo + head_base;
+
+    // the block's query rows (both planes) stay on chip for the whole walk: in registers for one row
+    // tile; for two, as MFMA operands in LDS (in the merge buffer, which is not needed before the end)
+    constexpr bool QLDS = NTQ > 1;
+    u32x4 qh[QLDS ? 1 : NTQ][KSTEPS], ql[QLDS ? 1 : NTQ][KSTEPS];
+    u32x4 *qs = (u32x4 *)&so[0][0][0];                               // [NTQ][2 planes][KSTEPS][64 lanes]
+    int rpos[NTQ];
+#pragma unroll
+    for (int q = 0; q < NTQ; ++q) {
+        const int j = j0 + q * 16 + n;
+        const bool valid = j < m;
+        rpos[q] = valid ? T + j : -1;
+        const int r = b * m + (valid ? j : j0);
+        if (!QLDS) {
+#pragma unroll
+            for (int s = 0; s < KSTEPS; ++s) {
+                const size_t off = xtile_off(r, h * DH + s * 32 + g * 8, d_model / 32);
+                qh[q][s] = *(const u32x4 *)((const bf16_t *)a.Qhi + off);
+                ql[q][s] = *(const u32x4 *)((const bf16_t *)a.Qlo + off);
+            }
+        } else {
+            for (int s = wave; s < KSTEPS; s += 4) {                 // (the four waves share the staging)
+                const size_t off = xtile_off(r, h * DH + s * 32 + g * 8, d_model / 32);
+                qs[((q * 2 + 0) * KSTEPS + s) * 64 + lane] = *(const u32x4 *)((const bf16_t *)a.Qhi + off);
+                qs[((q * 2 + 1) * KSTEPS + s) * 64 + lane] = *(const u32x4 *)((const bf16_t *)a.Qlo + off);
+            }
+        }
+    }
+    if (QLDS) __syncthreads();
+    f32x4 o[NTQ][DT];
+    float Mw[NTQ], Lw[NTQ];                                          // row n's running max; the lane's share of its running sum
+#pragma unroll
+    for (int q = 0; q < NTQ; ++q) {
+        Mw[q] = LLMA_NEG_INF; Lw[q] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) o[q][dt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
+    // one chunk of the wave; LO: the chunk has lo planes (a constant per call site, so that every load
+    // of the chunk is unconditional)
+    auto chunk = [&](int c, auto lo_tag) {
+        constexpr bool LO = decltype(lo_tag)::value;
+        const int key0 = c * ATTN_CHUNK + wave * 32;
+        if (key0 >= kv_len) return;                                  // uniform for the wave: no row sees these positions
+        u32x4 ka[2][KSTEPS], kb[2][KSTEPS], va[DT], vb[DT];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int s = 0; s < KSTEPS; ++s) {
+                const size_t off = (size_t)(key0 / 16 + t) * (16 * DH) + s * 512 + lane * 8;
+                ka[t][s] = *(const u32x4 *)(kh + off);
+                if (LO) kb[t][s] = *(const u32x4 *)(kl + off);
+            }
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            const size_t off = (size_t)(key0 / 32) * (32 * DH) + dt * 512 + lane * 8;
+            va[dt] = *(const u32x4 *)(vh + off);
+            if (LO) vb[dt] = *(const u32x4 *)(vl + off);
+        }
+#pragma unroll
+        for (int q = 0; q < NTQ; ++q) {
+            if (j0 + q * 16 >= m) continue;                          // a row tile past the block's rows (uniform)
+            float sv[8];
+            float mx = LLMA_NEG_INF;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s = 0; s < KSTEPS; ++s) {
+                    const u32x4 q_hi = QLDS ? qs[((q * 2 + 0) * KSTEPS + s) * 64 + lane] : qh[QLDS ? 0 : q][s];
+                    const u32x4 q_lo = QLDS ? qs[((q * 2 + 1) * KSTEPS + s) * 64 + lane] : ql[QLDS ? 0 : q][s];
+                    acc = mfma16x16x32(ka[t][s], q_hi, acc);
+                    acc = mfma16x16x32(ka[t][s], q_lo, acc);
+                    if (LO) acc = mfma16x16x32(kb[t][s], q_hi, acc);
+                }
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int key = key0 + t * 16 + 4 * g + r4;
+                    float v = acc[r4] * a.scale;
+                    v = (key > rpos[q]) ? LLMA_NEG_INF : v;
+                    sv[t * 4 + r4] = v;
+                    mx = fmaxf(mx, v);
+                }
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float Mn = fmaxf(Mw[q], mx);
+            const float s_old = (Mw[q] == LLMA_NEG_INF) ? 0.f : __expf(Mw[q] - Mn);     // (Mn = -inf only if both are)
+            float p[8], lsum = 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                p[i] = (Mn == LLMA_NEG_INF) ? 0.f : __expf(sv[i] - Mn);
+                lsum += p[i];
+            }
+            Lw[q] = Lw[q] * s_old + lsum;
+            Mw[q] = Mn;
+            u32x2 h0, l0, h1, l1;
+            split4(p, h0, l0);
+            split4(p + 4, h1, l1);
+            const u32x4 ph = (u32x4){h0[0], h0[1], h1[0], h1[1]};
+            const u32x4 pl = (u32x4){l0[0], l0[1], l1[0], l1[1]};
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                f32x4 od = o[q][dt] * s_old;
+                od = mfma16x16x32(va[dt], ph, od);
+                od = mfma16x16x32(va[dt], pl, od);
+                if (LO) od = mfma16x16x32(vb[dt], ph, od);
+                o[q][dt] = od;
+            }
+        }
+    };
+    for (int c = c0; c < c_lo; ++c) chunk(c, std::false_type{});
+    if (KVS)
+        for (int c = c_lo; c < c1; ++c) chunk(c, std::true_type{});
+
+    // publish the waves' states, merge them in wave order, write the walk's partial
+    if (QLDS) __syncthreads();                                       // every wave is done with the staged query rows
+#pragma unroll
+    for (int q = 0; q < NTQ; ++q) {
+        float lsum = Lw[q];
+        lsum += __shfl_xor(lsum, 16);
+        lsum += __shfl_xor(lsum, 32);
+        if (g == 0) { sm[wave][q * 16 + n] = Mw[q]; sl[wave][q * 16 + n] = lsum; }
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) *(f32x4 *)&so[wave][q * 16 + n][dt * 16 + 4 * g] = o[q][dt];
+    }
+    __syncthreads();
+    const size_t pbase = (((size_t)b * a.H + h) * a.n_chunks + blockIdx.x) * ((size_t)a.n_rblocks * RQ) + j0;
+#pragma unroll
+    for (int i = 0; i < OWN; ++i) {
+        const int idx = threadIdx.x + 256 * i;
+        if (idx < m_blk * (DH / 4)) {
+            const int j = idx / (DH / 4), d4 = idx % (DH / 4);
+            float Mc = LLMA_NEG_INF;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) Mc = fmaxf(Mc, sm[w][j]);
+            f32x4 accc = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float mw = sm[w][j];
+                const float sc = (mw == LLMA_NEG_INF) ? 0.f : __expf(mw - Mc);
+                accc += *(const f32x4 *)&so[w][j][d4 * 4] * sc;
+            }
+            *(f32x4 *)(a.po + (pbase + j) * DH + d4 * 4) = accc;
+        }
+    }
+    if (threadIdx.x < m_blk) {
+        const int j = threadIdx.x;
+        float Mc = LLMA_NEG_INF, Lc = 0.f;
+        for (int w = 0; w < 4; ++w) Mc = fmaxf(Mc, sm[w][j]);
+        for (int w = 0; w < 4; ++w) {
+            const float mw = sm[w][j];
+            Lc += (mw == LLMA_NEG_INF) ? 0.f : sl[w][j] * __expf(mw - Mc);
+        }
+        a.pm[pbase + j] = Mc;
+        a.pl[pbase + j] = Lc;
+    }
+}
+
 // merges the chunk partials of one (row, head): out = sum_c e^{m_c - M} O_c / sum_c e^{m_c - M} l_c,
 // over the chunks that contain positions <= the row's own, in chunk order; writes hi/lo tiled planes.
 // One thread per 4 output features; the partials of 16 chunks are in flight at a time.
@@ -1614,8 +1801,8 @@ static void launch_attn_dh(const AttnArgs &a0, hipStream_t st) {
         a.n_chunks = (a.n_chunks + ATTN_WALK_CHUNKS - 1) / ATTN_WALK_CHUNKS;
         a.part_span = ATTN_CHUNK * ATTN_WALK_CHUNKS;
         dim3 wgrid(a.n_chunks, a.H, a.n_seqs * a.n_rblocks);
-        if (ntq == 1) hipLaunchKernelGGL((attn_walk_bf16_kernel<DH, 1, KVS>), wgrid, dim3(256), 0, st, a);
-        else if (ntq == 2) hipLaunchKernelGGL((attn_walk_bf16_kernel<DH, 2, KVS>), wgrid, dim3(256), 0, st, a);
+        if (ntq == 1) hipLaunchKernelGGL((attn_walk_wave_bf16_kernel<DH, 1, KVS>), wgrid, dim3(256), 0, st, a);
+        else if (ntq == 2) hipLaunchKernelGGL((attn_walk_wave_bf16_kernel<DH, 2, KVS>), wgrid, dim3(256), 0, st, a);
         else hipLaunchKernelGGL((attn_walk_bf16_kernel<DH, 3, KVS>), wgrid, dim3(256), 0, st, a);
         hipLaunchKernelGGL((attn_combine_bf16_kernel<DH>), dim3(a.n_seqs * a.m, a.H), dim3(DH / 4), 0, st, a, a.n_rblocks * ntq * 16);
         return;
