@@ -215,7 +215,7 @@ def microbench(args, torch, synth, llma):
                         ev1.record()
                         torch.cuda.synchronize()
                         times.append(ev0.elapsed_time(ev1))
-                        assert kd == 0 or all(int(a) == want for a in na), (k, conv, mode, na)
+                        assert os.environ.get("LLMA_MB_NOCHECK") or kd == 0 or all(int(a) == want for a in na), (k, conv, mode, na)
                     ms = float(np.mean(times))
                     m = kd + 1
                     rows = B * m

@@ -1377,7 +1377,7 @@ __global__ __launch_bounds__(256, 2) void attn_walk_bf16_kernel(AttnArgs a) {
 // again a function of absolute positions only (wave w: positions 32 w .. 32 w + 31 of each chunk of
 // the walk in chunk order; then the waves in order; then the walks in order in the combine kernel).
 template <int DH, int NTQ, bool KVS>
-__global__ __launch_bounds__(256, (NTQ == 1 ? 4 : 2)) void attn_walk_wave_bf16_kernel(AttnArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_walk_wave_bf16_kernel(AttnArgs a) {
     constexpr int KSTEPS = DH / 32, DT = DH / 16;
     constexpr int RQ = NTQ * 16;
     constexpr int OWN = (RQ * (DH / 4) + 255) / 256;                  // merged output elements (float4) per thread
@@ -1461,6 +1461,7 @@ __global__ __launch_bounds__(256, (NTQ == 1 ? 4 : 2)) void attn_walk_wave_bf16_k
             va[dt] = *(const u32x4 *)(vh + off);
             if (LO) vb[dt] = *(const u32x4 *)(vl + off);
         }
+        __builtin_amdgcn_sched_barrier(0);                           // all of the chunk's blocks are in flight before the first is used
 #pragma unroll
         for (int q = 0; q < NTQ; ++q) {
             if (j0 + q * 16 >= m) continue;                          // a row tile past the block's rows (uniform)
