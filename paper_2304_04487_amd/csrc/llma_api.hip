@@ -356,7 +356,7 @@ static GemmArgs step_gemm_args(llma_ctx *c, int which, int layer, int rows) {
 // on the device's compute units (7B: one tile per workgroup for the 256-tile O / down matrices; 13B, 320
 // tiles: two, 35.6 -> 27.0 us for down; QKV 960 tiles: four, 34.0 -> 26.1 us).  So it is measured: every
 // admissible value, for 1 / 17 / 33 rows (one, two, three row tiles), on the context's own matrices and
-// zeroed scratch, a few dozen launches each; a value has to beat the default by 3 % to replace it.
+// zeroed scratch, a few dozen launches each; a value has to beat the default by 5 % to replace it.
 static int autotune_tilek(llma_ctx *c) {
     if (!c->bf16 || getenv("LLMA_NO_AUTOTUNE") != nullptr) return LLMA_OK;
     const llma_model_cfg &g = c->cfg;
@@ -400,7 +400,7 @@ static int autotune_tilek(llma_ctx *c) {
                 if (ft == dflt) dflt_us = us;
                 if (best_us == 0.f || us < best_us) { best_us = us; best = ft; }
             }
-            p.tk_ft[nt - 1] = (dflt_us > 0.f && best_us < 0.97f * dflt_us) ? best : dflt;
+            p.tk_ft[nt - 1] = (dflt_us > 0.f && best_us < 0.95f * dflt_us) ? best : dflt;
         }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
