@@ -561,6 +561,67 @@ def test_batched_step_after_import_and_prompt_rows(llma, k):
     ctx.close()
 
 
+@pytest.mark.parametrize("k,lens", [(16, [650, 140, 520, 129]), (24, [530, 129, 385]), (8, [650, 140, 520, 129, 300, 64, 511])],
+                         ids=["k16x4", "k24x3", "k8x7"])
+def test_wide_batched_steps_walk_several_chunks(llma, k, lens):
+    """Steps of more than 48 rows in all use the walking attention kernels: one row tile per sequence
+    (k = 8), two (k = 16, 24: query rows staged in LDS).  Sequences of 64..650 cached positions, so
+    walks of one to four chunks, one or two walks per sequence, a walk that ends inside a chunk; one
+    slot gets 40 computed rows on top of its imported cache (lo planes needed from there on).  Two
+    steps against the oracle: logits, accepted counts, next tokens, cache lengths."""
+    cfg = synth.ModelCfg("vb3", 3, 512, 4, 128, 1024, 4096, "bf16")
+    w = synth.make_weights(cfg, 10)
+    om = OracleModel(cfg, w)
+    B = len(lens)
+    slots = list(range(B))[::-1]
+    cap = 800
+    ctx = llma.Context(cfg, w, max_seq=cap, max_batch=B, max_k=k, kv_split=True)
+    ctx.enable_logits_dump(B * (k + 1))
+    assert B * (k + 1) > 48
+    caches, T, pend = [], [], []
+    for b, (slot, Tb) in enumerate(zip(slots, lens)):
+        cache = om.new_cache(cap)
+        for l in range(cfg.n_layers):
+            kk, vv = synth.make_kv_fill(cfg, 500 + b, 1, Tb, l)
+            cache.k[l][:, :Tb] = synth.bf16_to_f32(kk[0]).astype(np.float64)
+            cache.v[l][:, :Tb] = synth.bf16_to_f32(vv[0]).astype(np.float64)
+            ctx.kv_import(slot, l, torch.from_numpy(kk[0]).cuda(), torch.from_numpy(vv[0]).cuda(), Tb)
+        caches.append(cache); T.append(Tb); pend.append(21 + b)
+        ctx.set_pending(21 + b, slot)
+    more = synth.uniform_tokens(6, 78, 41, cfg.vocab)
+    ctx.prefill(more, slots[1])                                  # 40 computed rows on top of the second sequence's import
+    om.forward(more[:-1], caches[1], T[1])
+    T[1] += 40; pend[1] = int(more[-1])
+    assert ctx.get_state(slots[1]) == (T[1], pend[1])
+    for step in range(2):
+        drafts, wants, accs = [], [], []
+        for b in range(B):
+            d = synth.uniform_tokens(60 + step, b, k, cfg.vocab).tolist()
+            if b % 2 == 0:                                       # every other sequence: the first drafts are right
+                probe = om.new_cache(cap)
+                for l in range(cfg.n_layers):
+                    probe.k[l][:] = caches[b].k[l]; probe.v[l][:] = caches[b].v[l]
+                tok = pend[b]
+                for j in range(3):
+                    tok = int(argmax_tokens(om.forward([tok], probe, T[b] + j))[0]); d[j] = tok
+            want = om.forward([pend[b]] + d, caches[b], T[b])
+            o = argmax_tokens(want)
+            a = 0
+            while a < k and o[a] == d[a]:
+                a += 1
+            drafts.append(d); wants.append(want); accs.append((a, int(o[a])))
+        na, nxt, _ = ctx.verify_step_batch(slots, drafts)
+        got = ctx.logits(B * (k + 1)).reshape(B, k + 1, cfg.vocab)
+        for b in range(B):
+            check_logits(got[b], wants[b], f"wide step {step} seq {b} (T {T[b]})")
+            gaps_ok = all(top2_gap(wants[b][j]) > ATOL + RTOL * abs(float(wants[b][j].max())) for j in range(accs[b][0] + 1))
+            if gaps_ok:
+                assert (int(na[b]), int(nxt[b])) == accs[b], (step, b)
+            T[b] += int(na[b]) + 1; pend[b] = int(nxt[b])
+            assert ctx.get_state(slots[b]) == (T[b], pend[b])
+    ctx.close()
+
+
 # --------------------------------------------------------------------------- the verify-step microbenchmark at full size
 @pytest.mark.timeout(900)
 def test_verify_microbench_full_size(llma):
