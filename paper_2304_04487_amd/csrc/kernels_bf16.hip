@@ -322,7 +322,9 @@ __global__ __launch_bounds__((TileKShape<NT, FT>::MAX_THREADS)) void gemm_tilek_
     constexpr int SL = TileKShape<NT, FT>::SL;
     constexpr int TILES = (EPI == EPI_SWIGLU) ? 2 : 1;
     constexpr int AT = FT * TILES;                 // weight tiles per k-step
-    constexpr int UB = (AT * NT >= 4) ? 1 : 2;     // k-steps per load batch
+    // k-steps per load batch (two batches in flight): one weight tile and one row tile per wave (O, down at
+    // up to 16 rows: 256 workgroups, one per compute unit) need four for enough bytes in flight
+    constexpr int UB = (AT * NT >= 4) ? 1 : (AT * NT == 1 ? 4 : 2);
     constexpr int PL = SPLIT ? 2 : 1;
     extern __shared__ f32x4 red[];                 // [S][AT][NT][64], then rstd[16*NT] floats
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, S = (blockDim.x >> 6) * SL;
