@@ -625,7 +625,7 @@ def test_wide_batched_steps_walk_several_chunks(llma, k, lens):
 # --------------------------------------------------------------------------- the verify-step microbenchmark at full size
 @pytest.mark.timeout(900)
 def test_verify_microbench_full_size(llma):
-    """BASELINE configs[4] at its real size: LLaMA-7B shape, 16 sequences, 4096-position random KV
+    """The verification-step microbenchmark configuration at its real size: LLaMA-7B shape, 16 sequences, 4096-position random KV
     caches (N(0,1) rounded to bf16; the cache keeps hi + lo planes like everywhere else, because the
     step's own new rows need them to stay inside the logit tolerance at 32 layers), one
     verification step for all sequences.  Two sampled sequences are checked against the oracle
