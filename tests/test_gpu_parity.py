@@ -398,6 +398,38 @@ def test_ffn_gemm_timer_runs_and_checks_arguments(llma):
     ctx.close()
 
 
+def test_step_gemm_timer_covers_every_matrix_and_the_batched_form(llma):
+    """llma_time_step_gemm: every layer matrix and the LM head, at decoding-step row counts and at
+    more than 48 rows (the panel GEMM in its split-K form); bad arguments rejected; the context
+    decodes correctly again after a reset; llma_describe names the work division."""
+    cfg = MINI128
+    w = synth.make_weights(cfg, 4)
+    ctx = llma.Context(cfg, w, max_seq=96, max_batch=8, max_k=8)
+    text = ctx.describe()
+    assert "qkv" in text and "gate_up" in text and "lm_head" in text
+    for which in range(5):
+        for rows in (1, 9, 40, 72):
+            us = ctx.time_step_gemm(which, rows, 6)
+            assert 0.5 < us < 5000.0, (which, rows, us)
+    for which, rows, reps in ((-1, 4, 2), (5, 4, 2), (0, 0, 2), (0, 73, 2), (2, 4, 0)):      # 72 = max_batch (max_k + 1)
+        with pytest.raises(llma.LlmaError) as e:
+            ctx.time_step_gemm(which, rows, reps)
+        assert e.value.code == llma.LLMA_E_RANGE
+    om = OracleModel(cfg, w)
+    prompt = synth.uniform_tokens(9, 1, 30, cfg.vocab)
+    ctx.reset()
+    ctx.enable_logits_dump(4)
+    ctx.prefill(prompt)
+    cache = om.new_cache(96)
+    om.forward(prompt[:-1], cache, 0)
+    d = [3, 4, 5]
+    want = om.forward([int(prompt[-1])] + d, cache, len(prompt) - 1)
+    ctx.verify_step(d)
+    got = ctx.logits(4)
+    assert np.all(np.abs(got - want) <= BF16_ATOL + BF16_RTOL * np.abs(want))
+    ctx.close()
+
+
 def test_argument_errors_leave_context_unchanged(llma):
     cfg = synth.TINY
     w = synth.make_weights(cfg, 1)
