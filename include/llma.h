@@ -49,8 +49,9 @@ typedef struct {
     int32_t max_batch;     /* number of sequence slots                                      */
     int32_t max_k;         /* largest copy length k accepted by the step functions (<= 32)  */
     int32_t dtype;         /* LLMA_DTYPE_*                                                  */
-    int32_t kv_split;      /* bf16 only: 1 = keep K and V as hi + lo bf16 pairs (twice the cache
-                              bytes, 16 significand bits), 0 = one bf16 plane.  Ignored for fp32 */
+    int32_t kv_split;      /* bf16 only: 1 = keep K and V as a bf16 hi plane plus an 8-bit lo plane
+                              (the residual x - hi as fp8 e4m3 of 256 times it: 1.5 x the cache
+                              bytes, 12 significand bits), 0 = one bf16 plane.  Ignored for fp32 */
     float   rms_eps;       /* RMSNorm(x; g) = g * x / sqrt(mean(x^2) + rms_eps)              */
     float   rope_theta;    /* rotary base: feature i pairs with i + head_dim/2, angle
                               pos * rope_theta^(-2i/head_dim)                               */

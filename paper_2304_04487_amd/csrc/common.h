@@ -31,6 +31,32 @@ __device__ __forceinline__ void split4(const float v[4], u32x2 &hi, u32x2 &lo) {
     hi = (u32x2){(uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16)};
     lo = (u32x2){(uint32_t)l[0] | ((uint32_t)l[1] << 16), (uint32_t)l[2] | ((uint32_t)l[3] << 16)};
 }
+// ---- the 8-bit lo plane of the K/V cache ----------------------------------------------------
+// A cached value x is kept as hi = bf16(x) plus lo = x - hi.  |lo| <= ulp(hi) / 2 = 2^-9 |x| at most, and four
+// significant bits of it are enough (rounding lo to four bits costs a quarter of the logit tolerance at 32
+// layers, rounding it away eleven times the tolerance), so the lo plane holds one byte per element:
+// OCP fp8 e4m3 of 256 lo (|256 lo| <= |x|: saturates only for |x| > 448; spacing 2^-9 below 2^-6, i.e. lo is
+// kept to 2^-17 absolutely).  The attention kernels widen it to bf16 (exactly) in registers.
+__device__ __forceinline__ uint32_t lo8x2(float l0, float l1, uint32_t old, bool upper) {
+    const float a = fminf(fmaxf(l0 * 256.f, -448.f), 448.f), b = fminf(fmaxf(l1 * 256.f, -448.f), 448.f);
+    return upper ? (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)old, true)
+                 : (uint32_t)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)old, false);
+}
+__device__ __forceinline__ uint32_t lo8x4(const float l[4]) { return lo8x2(l[2], l[3], lo8x2(l[0], l[1], 0u, false), true); }
+__device__ __forceinline__ uint8_t lo8x1(float l) { return (uint8_t)(lo8x2(l, 0.f, 0u, false) & 0xffu); }
+// eight lo bytes (one lane's share of a block) -> the eight bf16 values the MFMA takes
+__device__ __forceinline__ u32x4 lo8_operand(u32x2 p) {
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    u32x4 r;
+#pragma unroll
+    for (int w = 0; w < 2; ++w) {
+        const f32x2_t a = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(p[w], 0.00390625f, false);
+        const f32x2_t b = __builtin_amdgcn_cvt_scalef32_pk_f32_fp8(p[w], 0.00390625f, true);
+        r[2 * w] = (__float_as_uint(a.x) >> 16) | (__float_as_uint(a.y) & 0xffff0000u);      // (at most four significant
+        r[2 * w + 1] = (__float_as_uint(b.x) >> 16) | (__float_as_uint(b.y) & 0xffff0000u);  //  bits: exact in bf16)
+    }
+    return r;
+}
 __device__ __forceinline__ f32x4 mfma16x16x32(u32x4 a, u32x4 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
                                                    __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);

@@ -78,8 +78,8 @@ void launch_pack_weight(const void *src, void *dst, int N, int K, int KSp, int r
 
 // plain [H][len][dh] bf16 -> tiled K / V cache of one (slot, layer); lo planes (if any) are zeroed
 __global__ void kv_import_bf16_kernel(const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
-                                      bf16_t *__restrict__ kh, bf16_t *__restrict__ kl,
-                                      bf16_t *__restrict__ vh, bf16_t *__restrict__ vl,
+                                      bf16_t *__restrict__ kh, uint8_t *__restrict__ kl,
+                                      bf16_t *__restrict__ vh, uint8_t *__restrict__ vl,
                                       int H, int len, int dh, int max_seq) {
     size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     size_t total = (size_t)H * len * dh;
@@ -99,7 +99,7 @@ void launch_kv_import_bf16(const void *k, const void *v, void *kh, void *kl, voi
     size_t total = (size_t)H * len * dh;
     unsigned blocks = (unsigned)((total + 255) / 256);
     hipLaunchKernelGGL(kv_import_bf16_kernel, dim3(blocks), dim3(256), 0, st, (const bf16_t *)k, (const bf16_t *)v,
-                       (bf16_t *)kh, (bf16_t *)kl, (bf16_t *)vh, (bf16_t *)vl, H, len, dh, max_seq);
+                       (bf16_t *)kh, (uint8_t *)kl, (bf16_t *)vh, (uint8_t *)vl, H, len, dh, max_seq);
 }
 
 // =============================================================================================
@@ -280,7 +280,11 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, const GemmPlan 
                     } else {
                         const size_t o = head_base + kcache_off(pos, c0, a.dh);
                         *(u32x2 *)((bf16_t *)a.k_hi + o) = hi;
-                        if (a.k_lo) *(u32x2 *)((bf16_t *)a.k_lo + o) = lo;
+                        if (a.k_lo) {                                   // one byte per element (see lo8x2)
+                            const float res[4] = {o4[0] - bf16_to_f32((bf16_t)(hi[0] & 0xffffu)), o4[1] - bf16_to_f32((bf16_t)(hi[0] >> 16)),
+                                                  o4[2] - bf16_to_f32((bf16_t)(hi[1] & 0xffffu)), o4[3] - bf16_to_f32((bf16_t)(hi[1] >> 16))};
+                            *(uint32_t *)((uint8_t *)a.k_lo + o) = lo8x4(res);
+                        }
                     }
                 }
             } else if (live) {
@@ -291,7 +295,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, const GemmPlan 
                     split_bf16(v[r], hi, lo);
                     const size_t o = head_base + vcache_off(pos, c0 + r, a.dh);
                     ((bf16_t *)a.v_hi)[o] = hi;
-                    if (a.v_lo) ((bf16_t *)a.v_lo)[o] = lo;
+                    if (a.v_lo) ((uint8_t *)a.v_lo)[o] = lo8x1(v[r] - bf16_to_f32(hi));
                 }
             }
         }
@@ -989,23 +993,24 @@ __device__ __forceinline__ void attn_chunk_body(const AttnArgs &a, float (&sm)[4
     loads_stay_above();
     // K and V blocks of the wave's 32 positions: issued before the sequence length is known (any
     // position below max_seq lies inside the cache allocation; unused blocks are simply dropped)
-    u32x4 ka[2][KSTEPS], kb[2][KSTEPS], va[DT], vb[DT];
+    u32x4 ka[2][KSTEPS], va[DT];
+        u32x2 kb[2][KSTEPS], vb[DT];                                 // lo planes: one byte per element
     {
-        const bf16_t *kh = (const bf16_t *)a.Khi + head_base, *kl = (const bf16_t *)a.Klo + head_base;
-        const bf16_t *vh = (const bf16_t *)a.Vhi + head_base, *vl = (const bf16_t *)a.Vlo + head_base;
+        const bf16_t *kh = (const bf16_t *)a.Khi + head_base; const uint8_t *kl = (const uint8_t *)a.Klo + head_base;
+        const bf16_t *vh = (const bf16_t *)a.Vhi + head_base; const uint8_t *vl = (const uint8_t *)a.Vlo + head_base;
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int s = 0; s < KSTEPS; ++s) {
                 const size_t off = (size_t)(key0 / 16 + t) * (16 * DH) + s * 512 + lane * 8;
                 ka[t][s] = *(const u32x4 *)(kh + off);
-                if (KVS) kb[t][s] = (*(const u32x4 *)(kl + off));
+                if (KVS) kb[t][s] = *(const u32x2 *)(kl + off);
             }
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
             const size_t off = (size_t)(key0 / 32) * (32 * DH) + dt * 512 + lane * 8;
             va[dt] = (*(const u32x4 *)(vh + off));
-            if (KVS) vb[dt] = (*(const u32x4 *)(vl + off));
+            if (KVS) vb[dt] = *(const u32x2 *)(vl + off);
         }
     }
     // a single row tile's query operands do not depend on the sequence length either
@@ -1085,7 +1090,7 @@ __device__ __forceinline__ void attn_chunk_body(const AttnArgs &a, float (&sm)[4
                 for (int s = 0; s < KSTEPS; ++s) {
                     acc = mfma16x16x32(ka[t][s], qh[s], acc);
                     acc = mfma16x16x32(ka[t][s], ql[s], acc);
-                    if (KVS) acc = mfma16x16x32(kb[t][s], qh[s], acc);
+                    if (KVS) acc = mfma16x16x32(lo8_operand(kb[t][s]), qh[s], acc);
                 }
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
@@ -1116,7 +1121,7 @@ __device__ __forceinline__ void attn_chunk_body(const AttnArgs &a, float (&sm)[4
             for (int dt = 0; dt < DT; ++dt) {
                 o[oi][dt] = mfma16x16x32(va[dt], ph, o[oi][dt]);
                 o[oi][dt] = mfma16x16x32(va[dt], pl, o[oi][dt]);
-                if (KVS) o[oi][dt] = mfma16x16x32(vb[dt], ph, o[oi][dt]);
+                if (KVS) o[oi][dt] = mfma16x16x32(lo8_operand(vb[dt]), ph, o[oi][dt]);
             }
             if (COMPACT) {
                 publish(q, o[0]);
@@ -1218,8 +1223,8 @@ __global__ __launch_bounds__(256, 2) void attn_walk_bf16_kernel(AttnArgs a) {
     c_lo = c_lo < c0 ? c0 : (c_lo > c1 ? c1 : c_lo);
     const int d_model = a.H * DH;
     const size_t head_base = ((size_t)slot * a.H + h) * (size_t)a.max_seq * DH;
-    const bf16_t *kh = (const bf16_t *)a.Khi + head_base, *kl = (const bf16_t *)a.Klo + head_base;
-    const bf16_t *vh = (const bf16_t *)a.Vhi + head_base, *vl = (const bf16_t *)a.Vlo + head_base;
+    const bf16_t *kh = (const bf16_t *)a.Khi + head_base; const uint8_t *kl = (const uint8_t *)a.Klo + head_base;
+    const bf16_t *vh = (const bf16_t *)a.Vhi + head_base; const uint8_t *vl = (const uint8_t *)a.Vlo + head_base;
 
     f32x4 acc_run[OWN];
     float M_run[OWN];
@@ -1230,7 +1235,8 @@ __global__ __launch_bounds__(256, 2) void attn_walk_bf16_kernel(AttnArgs a) {
         const int key0 = c * ATTN_CHUNK + wave * 32;
         const bool active = key0 < kv_len;                           // uniform for the wave
         const bool use_lo = KVS && c >= c_lo;                        // uniform for the workgroup
-        u32x4 ka[2][KSTEPS], kb[2][KSTEPS], va[DT], vb[DT];
+        u32x4 ka[2][KSTEPS], va[DT];
+        u32x2 kb[2][KSTEPS], vb[DT];                                 // lo planes: one byte per element
         if (active) {
 #pragma unroll
             for (int t = 0; t < 2; ++t)
@@ -1238,13 +1244,13 @@ __global__ __launch_bounds__(256, 2) void attn_walk_bf16_kernel(AttnArgs a) {
                 for (int s = 0; s < KSTEPS; ++s) {
                     const size_t off = (size_t)(key0 / 16 + t) * (16 * DH) + s * 512 + lane * 8;
                     ka[t][s] = *(const u32x4 *)(kh + off);
-                    if (KVS && use_lo) kb[t][s] = *(const u32x4 *)(kl + off);
+                    if (KVS && use_lo) kb[t][s] = *(const u32x2 *)(kl + off);
                 }
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) {
                 const size_t off = (size_t)(key0 / 32) * (32 * DH) + dt * 512 + lane * 8;
                 va[dt] = *(const u32x4 *)(vh + off);
-                if (KVS && use_lo) vb[dt] = *(const u32x4 *)(vl + off);
+                if (KVS && use_lo) vb[dt] = *(const u32x2 *)(vl + off);
             }
         }
 #pragma unroll
@@ -1274,7 +1280,7 @@ __global__ __launch_bounds__(256, 2) void attn_walk_bf16_kernel(AttnArgs a) {
                     for (int s = 0; s < KSTEPS; ++s) {
                         acc = mfma16x16x32(ka[t][s], qh[s], acc);
                         acc = mfma16x16x32(ka[t][s], ql[s], acc);
-                        if (KVS && use_lo) acc = mfma16x16x32(kb[t][s], qh[s], acc);
+                        if (KVS && use_lo) acc = mfma16x16x32(lo8_operand(kb[t][s]), qh[s], acc);
                     }
 #pragma unroll
                     for (int r4 = 0; r4 < 4; ++r4) {
@@ -1303,7 +1309,7 @@ __global__ __launch_bounds__(256, 2) void attn_walk_bf16_kernel(AttnArgs a) {
                 for (int dt = 0; dt < DT; ++dt) {
                     o[dt] = mfma16x16x32(va[dt], ph, o[dt]);
                     o[dt] = mfma16x16x32(va[dt], pl, o[dt]);
-                    if (KVS && use_lo) o[dt] = mfma16x16x32(vb[dt], ph, o[dt]);
+                    if (KVS && use_lo) o[dt] = mfma16x16x32(lo8_operand(vb[dt]), ph, o[dt]);
                 }
             }
             // publish this wave's (max, sum, O) of the row tile
@@ -1403,8 +1409,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     c_lo = c_lo < c0 ? c0 : (c_lo > c1 ? c1 : c_lo);
     const int d_model = a.H * DH;
     const size_t head_base = ((size_t)slot * a.H + h) * (size_t)a.max_seq * DH;
-    const bf16_t *kh = (const bf16_t *)a.Khi + head_base, *kl = (const bf16_t *)a.Klo + head_base;
-    const bf16_t *vh = (const bf16_t *)a.Vhi + head_base, *vl = (const bf16_t *)a.Vlo + head_base;
+    const bf16_t *kh = (const bf16_t *)a.Khi + head_base; const uint8_t *kl = (const uint8_t *)a.Klo + head_base;
+    const bf16_t *vh = (const bf16_t *)a.Vhi + head_base; const uint8_t *vl = (const uint8_t *)a.Vlo + head_base;
 
     // the block's query rows (both planes) stay on chip for the whole walk: in registers for one row
     // tile; for two, as MFMA operands in LDS (in the merge buffer, which is not needed before the end)
@@ -1448,20 +1454,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         constexpr bool LO = decltype(lo_tag)::value;
         const int key0 = c * ATTN_CHUNK + wave * 32;
         if (key0 >= kv_len) return;                                  // uniform for the wave: no row sees these positions
-        u32x4 ka[2][KSTEPS], kb[2][KSTEPS], va[DT], vb[DT];
+        u32x4 ka[2][KSTEPS], va[DT];
+        u32x2 kb[2][KSTEPS], vb[DT];                                 // lo planes: one byte per element
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int s = 0; s < KSTEPS; ++s) {
                 const size_t off = (size_t)(key0 / 16 + t) * (16 * DH) + s * 512 + lane * 8;
                 ka[t][s] = *(const u32x4 *)(kh + off);
-                if (LO) kb[t][s] = *(const u32x4 *)(kl + off);
+                if (LO) kb[t][s] = *(const u32x2 *)(kl + off);
             }
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
             const size_t off = (size_t)(key0 / 32) * (32 * DH) + dt * 512 + lane * 8;
             va[dt] = *(const u32x4 *)(vh + off);
-            if (LO) vb[dt] = *(const u32x4 *)(vl + off);
+            if (LO) vb[dt] = *(const u32x2 *)(vl + off);
         }
         __builtin_amdgcn_sched_barrier(0);                           // all of the chunk's blocks are in flight before the first is used
 #pragma unroll
@@ -1478,7 +1485,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                     const u32x4 q_lo = QLDS ? qs[((q * 2 + 1) * KSTEPS + s) * 64 + lane] : ql[QLDS ? 0 : q][s];
                     acc = mfma16x16x32(ka[t][s], q_hi, acc);
                     acc = mfma16x16x32(ka[t][s], q_lo, acc);
-                    if (LO) acc = mfma16x16x32(kb[t][s], q_hi, acc);
+                    if (LO) acc = mfma16x16x32(lo8_operand(kb[t][s]), q_hi, acc);
                 }
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
@@ -1511,7 +1518,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 f32x4 od = o[q][dt] * s_old;
                 od = mfma16x16x32(va[dt], ph, od);
                 od = mfma16x16x32(va[dt], pl, od);
-                if (LO) od = mfma16x16x32(vb[dt], ph, od);
+                if (LO) od = mfma16x16x32(lo8_operand(vb[dt]), ph, od);
                 o[q][dt] = od;
             }
         }
@@ -1649,8 +1656,8 @@ __global__ __launch_bounds__(256) void attn_prompt_bf16_kernel(AttnArgs a) {
     const int m_blk = (m - j0 < RQ) ? m - j0 : RQ;
     const int d_model = a.H * DH;
     const size_t head_base = ((size_t)slot * a.H + h) * (size_t)a.max_seq * DH;
-    const bf16_t *kh = (const bf16_t *)a.Khi + head_base, *kl = (const bf16_t *)a.Klo + head_base;
-    const bf16_t *vh = (const bf16_t *)a.Vhi + head_base, *vl = (const bf16_t *)a.Vlo + head_base;
+    const bf16_t *kh = (const bf16_t *)a.Khi + head_base; const uint8_t *kl = (const uint8_t *)a.Klo + head_base;
+    const bf16_t *vh = (const bf16_t *)a.Vhi + head_base; const uint8_t *vl = (const uint8_t *)a.Vlo + head_base;
     const int T = a.T[slot];
     const int kv_len = T + j0 + m_blk;                  // positions the block's last row can see
     const int n_ch = (kv_len + ATTN_CHUNK - 1) / ATTN_CHUNK;
@@ -1668,7 +1675,7 @@ __global__ __launch_bounds__(256) void attn_prompt_bf16_kernel(AttnArgs a) {
             ql[q][s] = *(const u32x4 *)((const bf16_t *)a.Qlo + off);
         }
     }
-    auto fetch = [&](int c, u32x4 (&ka)[2][KSTEPS], u32x4 (&kb)[2][KSTEPS], u32x4 (&va)[DT], u32x4 (&vb)[DT]) {
+    auto fetch = [&](int c, u32x4 (&ka)[2][KSTEPS], u32x2 (&kb)[2][KSTEPS], u32x4 (&va)[DT], u32x2 (&vb)[DT]) {
         const int key0 = c * ATTN_CHUNK + wave * 32;    // below the rounded capacity for every launched chunk
 #pragma unroll
         for (int t = 0; t < 2; ++t)
@@ -1676,13 +1683,13 @@ __global__ __launch_bounds__(256) void attn_prompt_bf16_kernel(AttnArgs a) {
             for (int s = 0; s < KSTEPS; ++s) {
                 const size_t off = (size_t)(key0 / 16 + t) * (16 * DH) + s * 512 + lane * 8;
                 ka[t][s] = *(const u32x4 *)(kh + off);
-                if (KVS) kb[t][s] = *(const u32x4 *)(kl + off);
+                if (KVS) kb[t][s] = *(const u32x2 *)(kl + off);
             }
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
             const size_t off = (size_t)(key0 / 32) * (32 * DH) + dt * 512 + lane * 8;
             va[dt] = *(const u32x4 *)(vh + off);
-            if (KVS) vb[dt] = *(const u32x4 *)(vl + off);
+            if (KVS) vb[dt] = *(const u32x2 *)(vl + off);
         }
     };
     float mrow[NTQ], lrow[NTQ];
@@ -1694,7 +1701,7 @@ __global__ __launch_bounds__(256) void attn_prompt_bf16_kernel(AttnArgs a) {
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) o[q][dt] = (f32x4){0.f, 0.f, 0.f, 0.f};
     }
-    auto consume = [&](int c, u32x4 (&ka)[2][KSTEPS], u32x4 (&kb)[2][KSTEPS], u32x4 (&va)[DT], u32x4 (&vb)[DT]) {
+    auto consume = [&](int c, u32x4 (&ka)[2][KSTEPS], u32x2 (&kb)[2][KSTEPS], u32x4 (&va)[DT], u32x2 (&vb)[DT]) {
         const int key0 = c * ATTN_CHUNK + wave * 32;
         if (key0 >= kv_len) return;                     // uniform for the wave
 #pragma unroll
@@ -1708,7 +1715,7 @@ __global__ __launch_bounds__(256) void attn_prompt_bf16_kernel(AttnArgs a) {
                 for (int s = 0; s < KSTEPS; ++s) {
                     acc = mfma16x16x32(ka[t][s], qh[q][s], acc);
                     acc = mfma16x16x32(ka[t][s], ql[q][s], acc);
-                    if (KVS) acc = mfma16x16x32(kb[t][s], qh[q][s], acc);
+                    if (KVS) acc = mfma16x16x32(lo8_operand(kb[t][s]), qh[q][s], acc);
                 }
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
@@ -1742,11 +1749,12 @@ __global__ __launch_bounds__(256) void attn_prompt_bf16_kernel(AttnArgs a) {
                 o[q][dt] *= alpha;
                 o[q][dt] = mfma16x16x32(va[dt], ph, o[q][dt]);
                 o[q][dt] = mfma16x16x32(va[dt], pl, o[q][dt]);
-                if (KVS) o[q][dt] = mfma16x16x32(vb[dt], ph, o[q][dt]);
+                if (KVS) o[q][dt] = mfma16x16x32(lo8_operand(vb[dt]), ph, o[q][dt]);
             }
         }
     };
-    u32x4 kaA[2][KSTEPS], kbA[2][KSTEPS], vaA[DT], vbA[DT], kaB[2][KSTEPS], kbB[2][KSTEPS], vaB[DT], vbB[DT];
+    u32x4 kaA[2][KSTEPS], vaA[DT], kaB[2][KSTEPS], vaB[DT];
+    u32x2 kbA[2][KSTEPS], vbA[DT], kbB[2][KSTEPS], vbB[DT];
     fetch(0, kaA, kbA, vaA, vbA);
     for (int c = 0; c < n_ch; c += 2) {
         if (c + 1 < n_ch) fetch(c + 1, kaB, kbB, vaB, vbB);

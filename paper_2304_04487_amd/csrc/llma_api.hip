@@ -212,10 +212,10 @@ static int create_impl(llma_ctx *c, const llma_weights *w) {
         HIP_TRY(c, hipMemsetAsync(c->kc[l], 0, kv_bytes, c->st));
         HIP_TRY(c, hipMemsetAsync(c->vc[l], 0, kv_bytes, c->st));
         if (c->kv_split) {
-            ALLOC(c, c->kc_lo[l], kv_bytes);
-            ALLOC(c, c->vc_lo[l], kv_bytes);
-            HIP_TRY(c, hipMemsetAsync(c->kc_lo[l], 0, kv_bytes, c->st));
-            HIP_TRY(c, hipMemsetAsync(c->vc_lo[l], 0, kv_bytes, c->st));
+            ALLOC(c, c->kc_lo[l], kv_bytes / 2);                  // lo planes: one byte per element
+            ALLOC(c, c->vc_lo[l], kv_bytes / 2);
+            HIP_TRY(c, hipMemsetAsync(c->kc_lo[l], 0, kv_bytes / 2, c->st));
+            HIP_TRY(c, hipMemsetAsync(c->vc_lo[l], 0, kv_bytes / 2, c->st));
         }
     }
     // ---- rotary table: cos/sin(pos * theta^(-2i/dh)) in double, stored fp32
@@ -717,7 +717,7 @@ extern "C" int llma_kv_import(llma_ctx *c, int32_t seq, int32_t layer, const voi
     const size_t es = c->bf16 ? 2 : 4;
     const size_t slot_off = (size_t)seq * g.n_heads * c->seq_cap * g.head_dim * es;
     void *kc = (char *)c->kc[layer] + slot_off, *vc = (char *)c->vc[layer] + slot_off;
-    void *kl = c->kv_split ? (char *)c->kc_lo[layer] + slot_off : nullptr, *vl = c->kv_split ? (char *)c->vc_lo[layer] + slot_off : nullptr;
+    void *kl = c->kv_split ? (char *)c->kc_lo[layer] + slot_off / 2 : nullptr, *vl = c->kv_split ? (char *)c->vc_lo[layer] + slot_off / 2 : nullptr;
     if (len > 0) {
         if (c->bf16) launch_kv_import_bf16(k, v, kc, kl, vc, vl, g.n_heads, len, g.head_dim, c->seq_cap, c->st);
         else launch_kv_import_f32(k, v, kc, vc, g.n_heads, len, g.head_dim, c->seq_cap, c->st);
