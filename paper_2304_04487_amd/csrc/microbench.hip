@@ -5,6 +5,9 @@
 //                              per workgroup x waves) next to a plain streaming read of the same bytes
 //   llma_microbench timeline   per-wave time stamps inside one tile-K launch: kernel entry, first
 //                              operands arrived, end of the K loop, end of the epilogue
+//   llma_microbench side-branch  the four GEMMs of a layer back to back on one stream, with and without a second stream that
+//                              reads the first megabytes of the NEXT GEMM's weights while the current one runs (what a
+//                              side branch of a captured graph would do)
 //   llma_microbench two-phase  two weight-streaming phases (gate/up then down, ...) as two kernels back
 //                              to back, as one kernel, and as one kernel with a grid-wide barrier between
 //                              the phases (with / without agent-scope fences, with / without requesting the
@@ -217,6 +220,66 @@ static void cmd_timeline() {
 }
 #endif
 
+// ------------------------------------------------------------------------------------------------ side-branch
+#ifndef MICROBENCH_TIMELINE
+template <int EPI, int FT>
+static void launch_tilek_on(GemmArgs a, int waves, hipStream_t st) {
+    constexpr int TILES = (EPI == EPI_SWIGLU) ? 2 : 1;
+    const size_t lds = (size_t)waves * FT * TILES * 1024 + 256;
+    static std::atomic<uint64_t> done{0};
+    allow_full_lds((const void *)gemm_tilek_bf16<1, EPI, true, FT>, done);
+    hipLaunchKernelGGL((gemm_tilek_bf16<1, EPI, true, FT>), dim3((a.plan.tasks + FT - 1) / FT), dim3(waves * 64), lds, st, a);
+}
+static void cmd_side_branch() {
+    Bufs b = make_bufs();
+    hipStream_t s0, s1;
+    CK(hipStreamCreate(&s0)); CK(hipStreamCreate(&s1));                 // (default priority)
+    const int L = 24, NK = 4 * L;                                        // 24 "layers" of four GEMMs, weights from rotating addresses
+    std::vector<hipEvent_t> ev(NK);
+    for (auto &e : ev) CK(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    size_t bytes[4]; GemmArgs args[4];
+    const int order[4] = {0, 1, 2, 3};                                   // qkv, o, gate/up, down
+    size_t layer_bytes = 0;
+    for (int i = 0; i < 4; ++i) { args[i] = make_args(SHAPES[order[i]], b, 1, bytes[i]); layer_bytes += (bytes[i] + 4095) & ~(size_t)4095; }
+    const int n_slots = (int)(W_BYTES / layer_bytes);
+    auto weights = [&](int k) {                                          // kernel k of the chain -> its weights
+        const int l = k / 4, i = k % 4;
+        size_t off = (size_t)(l % n_slots) * layer_bytes;
+        for (int j = 0; j < i; ++j) off += (bytes[j] + 4095) & ~(size_t)4095;
+        return wbuf + off;
+    };
+    auto launch = [&](int k, hipStream_t st) {
+        GemmArgs a = args[k % 4]; a.W = weights(k);
+        switch (k % 4) {
+            case 0: launch_tilek_on<EPI_QKV, 3>(a, 16, st); break;
+            case 1: launch_tilek_on<EPI_RESID, 1>(a, 8, st); break;
+            case 2: launch_tilek_on<EPI_SWIGLU, 1>(a, 8, st); break;
+            default: launch_tilek_on<EPI_RESID, 1>(a, 8, st); break;
+        }
+    };
+    for (size_t pre_mb : {(size_t)0, (size_t)4, (size_t)16, (size_t)64}) {
+        float best = 1e9f;
+        for (int pass = 0; pass < 3; ++pass) {
+            CK(hipDeviceSynchronize());
+            CK(hipEventRecord(e0, s0));
+            for (int k = 0; k < NK; ++k) {
+                if (pre_mb && k + 1 < NK) {                              // the side branch: starts when kernel k - 1 is done, like kernel k
+                    if (k > 0) CK(hipStreamWaitEvent(s1, ev[k - 1], 0));
+                    const size_t n16 = std::min(pre_mb << 20, bytes[(k + 1) % 4]) / 16;
+                    hipLaunchKernelGGL(touch_kernel, dim3(64), dim3(256), 0, s1, (const u32x4 *)weights(k + 1), n16, b.sink);
+                }
+                launch(k, s0);
+                if (pre_mb) CK(hipEventRecord(ev[k], s0));
+            }
+            CK(hipEventRecord(e1, s0)); CK(hipEventSynchronize(e1)); CK(hipStreamSynchronize(s1)); CK(hipGetLastError());
+            float ms; CK(hipEventElapsedTime(&ms, e0, e1));
+            if (pass) best = std::min(best, ms / L * 1e3f);
+        }
+        printf("four GEMMs of a layer at one row, %2d layers back to back, next GEMM's first %2zu MB read on a second stream: %7.2f us per layer\n", L, pre_mb, best);
+    }
+}
+#endif
+
 // ------------------------------------------------------------------------------------------------ two-phase
 #ifndef MICROBENCH_TIMELINE
 struct Bar { unsigned *cnt; unsigned *grp; unsigned *err; };
@@ -370,7 +433,8 @@ int main(int argc, char **argv) {
     const char *cmd = argc > 1 ? argv[1] : "";
     if (!strcmp(cmd, "shapes")) cmd_shapes();
     else if (!strcmp(cmd, "two-phase")) cmd_two_phase();
-    else { printf("usage: llma_microbench shapes | two-phase      (llma_microbench_timeline for the per-wave time stamps)\n"); return 2; }
+    else if (!strcmp(cmd, "side-branch")) cmd_side_branch();
+    else { printf("usage: llma_microbench shapes | two-phase | side-branch      (llma_microbench_timeline for the per-wave time stamps)\n"); return 2; }
 #endif
     return 0;
 }
