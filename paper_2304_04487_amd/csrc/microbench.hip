@@ -8,6 +8,8 @@
 //   llma_microbench side-branch  the four GEMMs of a layer back to back on one stream, with and without a second stream that
 //                              reads the first megabytes of the NEXT GEMM's weights while the current one runs (what a
 //                              side branch of a captured graph would do)
+//   llma_microbench lo8         the one-byte lo plane of the K/V cache: the library's encode / widen helpers on 3462 values
+//                              against a host model of OCP fp8 e4m3 (round to nearest even, subnormals, saturation)
 //   llma_microbench two-phase  two weight-streaming phases (gate/up then down, ...) as two kernels back
 //                              to back, as one kernel, and as one kernel with a grid-wide barrier between
 //                              the phases (with / without agent-scope fences, with / without requesting the
@@ -35,6 +37,7 @@ __device__ unsigned long long pn_trace[(size_t)PN_WG * 8 * 64 * 4];
 #include "kernels_bf16.hip"
 
 #include <stdio.h>
+#include <math.h>
 #include <string.h>
 #include <algorithm>
 #include <vector>
@@ -217,6 +220,49 @@ static void cmd_timeline() {
         timeline_one<EPI_SWIGLU, 1>(SHAPES[2], b, rows, 8);
         timeline_one<EPI_RESID, 1>(SHAPES[3], b, rows, 8);
     }
+}
+#endif
+
+// ------------------------------------------------------------------------------------------------ lo8
+#ifndef MICROBENCH_TIMELINE
+__global__ void lo8_roundtrip_kernel(const float *in, float *out, int n) {       // n a multiple of 8
+    const int i = (blockIdx.x * blockDim.x + threadIdx.x) * 8;
+    if (i + 7 >= n) return;
+    const float a[4] = {in[i], in[i + 1], in[i + 2], in[i + 3]}, c[4] = {in[i + 4], in[i + 5], in[i + 6], in[i + 7]};
+    const u32x4 w = lo8_operand((u32x2){lo8x4(a), lo8x4(c)});                     // eight bf16 values
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        out[i + 2 * j] = __uint_as_float(w[j] << 16);
+        out[i + 2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
+    }
+}
+static double e4m3_model(double y) {                    // OCP fp8 e4m3fn: 3 mantissa bits, spacing 2^-9 below 2^-6, largest value 448
+    if (y > 448) y = 448;
+    if (y < -448) y = -448;
+    if (y == 0) return 0;
+    int e; frexp(y, &e);
+    if (e < -5) e = -5;
+    double q = nearbyint(ldexp(y, 4 - e)) * ldexp(1.0, e - 4);
+    return q > 448 ? 448 : (q < -448 ? -448 : q);
+}
+static void cmd_lo8() {
+    std::vector<float> h;
+    for (int e = -24; e <= 2; ++e) for (int m = 0; m < 64; ++m) { const float v = ldexpf(1.f + m / 64.f, e); h.push_back(v); h.push_back(-v); }
+    for (float v : {0.f, -0.f, 1.75f, 2.f, 1e-30f, 3.f}) h.push_back(v);
+    while (h.size() % 8) h.push_back(0.f);
+    const int n = (int)h.size();
+    float *din, *dout; CK(hipMalloc(&din, n * 4)); CK(hipMalloc(&dout, n * 4));
+    CK(hipMemcpy(din, h.data(), n * 4, hipMemcpyHostToDevice));
+    hipLaunchKernelGGL(lo8_roundtrip_kernel, dim3((n / 8 + 63) / 64), dim3(64), 0, 0, din, dout, n);
+    CK(hipDeviceSynchronize());
+    std::vector<float> d(n); CK(hipMemcpy(d.data(), dout, n * 4, hipMemcpyDeviceToHost));
+    int bad = 0;
+    for (int i = 0; i < n; ++i) {
+        const double want = e4m3_model((double)h[i] * 256.0) / 256.0;
+        if ((double)d[i] != want && bad++ < 10) printf("lo = %.9g: device %.9g, host model %.9g\n", h[i], d[i], want);
+    }
+    printf("lo8: %d residuals through lo8x4 + lo8_operand (fp8 e4m3 of 256 lo, widened to bf16): %d differ from the host model\n", n, bad);
+    if (bad) exit(1);
 }
 #endif
 
@@ -424,7 +470,7 @@ static void cmd_two_phase() {
 #endif
 
 int main(int argc, char **argv) {
-    CK(hipMalloc(&wbuf, W_BYTES)); CK(hipMemset(wbuf, 0x11, W_BYTES));
+    if (!(argc > 1 && !strcmp(argv[1], "lo8"))) { CK(hipMalloc(&wbuf, W_BYTES)); CK(hipMemset(wbuf, 0x11, W_BYTES)); }   // (lo8 streams no weights)
     CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
 #ifdef MICROBENCH_TIMELINE
     if (argc > 1 && !strcmp(argv[1], "panel")) cmd_panel();
@@ -434,7 +480,8 @@ int main(int argc, char **argv) {
     if (!strcmp(cmd, "shapes")) cmd_shapes();
     else if (!strcmp(cmd, "two-phase")) cmd_two_phase();
     else if (!strcmp(cmd, "side-branch")) cmd_side_branch();
-    else { printf("usage: llma_microbench shapes | two-phase | side-branch      (llma_microbench_timeline for the per-wave time stamps)\n"); return 2; }
+    else if (!strcmp(cmd, "lo8")) cmd_lo8();
+    else { printf("usage: llma_microbench shapes | two-phase | side-branch | lo8      (llma_microbench_timeline for the per-wave time stamps)\n"); return 2; }
 #endif
     return 0;
 }

@@ -7,6 +7,8 @@ Bars:
   - emitted tokens identical to the oracle's except where the oracle's top-2 logit gap is
     below that tolerance; every such near-tie is printed.
 """
+import os
+
 import numpy as np
 import pytest
 
@@ -428,6 +430,17 @@ def test_step_gemm_timer_covers_every_matrix_and_the_batched_form(llma):
     got = ctx.logits(4)
     assert np.all(np.abs(got - want) <= BF16_ATOL + BF16_RTOL * np.abs(want))
     ctx.close()
+
+
+def test_lo_plane_bytes_match_a_host_model_of_e4m3():
+    """The one-byte lo plane of the K/V cache: the library's own encode and widen helpers (built into the
+    stand-alone tool beside the library) on 3464 residuals against a host model of OCP fp8 e4m3 --
+    round to nearest even, subnormals, saturation at 448."""
+    import subprocess
+    tool = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2304_04487_amd", "tools", "llma_microbench")
+    assert os.path.exists(tool), "paper_2304_04487_amd/tools/llma_microbench is not built (python paper_2304_04487_amd/build.py)"
+    r = subprocess.run([tool, "lo8"], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120)
+    assert r.returncode == 0 and ": 0 differ from the host model" in r.stdout, r.stdout[-600:]
 
 
 def test_argument_errors_leave_context_unchanged(llma):
