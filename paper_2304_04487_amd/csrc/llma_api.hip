@@ -379,10 +379,8 @@ static int autotune_tilek(llma_ctx *c) {
             if (rows > step_rows || rows > 48) continue;                  // this context never launches that many row tiles
             GemmPlan &p = *plans[which];
             const int dflt = p.tk_ft[nt - 1];
-            float best_us = 0.f, dflt_us = 0.f;
-            int best = dflt;
-            for (int ft = 1; ft <= 4; ++ft) {
-                if (!tilek_ft_valid(p, nt, ft)) continue;
+            // mean launch time of this matrix at `rows` rows with FT = ft
+            auto time_ft = [&](int ft, float *us) -> int {
                 p.tk_ft[nt - 1] = ft;
                 float ms = 0.f;
                 for (int pass = 0; pass < 2; ++pass) {                    // pass 0 warms up
@@ -396,11 +394,29 @@ static int autotune_tilek(llma_ctx *c) {
                     HIP_TRY(c, hipEventSynchronize(e1));
                     HIP_TRY(c, hipEventElapsedTime(&ms, e0, e1));
                 }
-                const float us = ms * 1e3f / reps;
+                *us = ms * 1e3f / reps;
+                return LLMA_OK;
+            };
+            float best_us = 0.f, dflt_us = 0.f;
+            int best = dflt;
+            for (int ft = 1; ft <= 4; ++ft) {
+                if (!tilek_ft_valid(p, nt, ft)) continue;
+                float us = 0.f;
+                if (int rc = time_ft(ft, &us)) return rc;
                 if (ft == dflt) dflt_us = us;
                 if (best_us == 0.f || us < best_us) { best_us = us; best = ft; }
             }
-            p.tk_ft[nt - 1] = (dflt_us > 0.f && best_us < 0.95f * dflt_us) ? best : dflt;
+            // A candidate replaces the default only if it wins by 5 % twice: in the sweep and again
+            // head to head (default first, candidate second), so that one disturbed measurement
+            // -- clocks still ramping, another process on the card -- cannot pick a slower shape.
+            bool adopt = best != dflt && dflt_us > 0.f && best_us < 0.95f * dflt_us;
+            if (adopt) {
+                float d2 = 0.f, b2 = 0.f;
+                if (int rc = time_ft(dflt, &d2)) return rc;
+                if (int rc = time_ft(best, &b2)) return rc;
+                adopt = b2 < 0.95f * d2;
+            }
+            p.tk_ft[nt - 1] = adopt ? best : dflt;
         }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
