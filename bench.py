@@ -177,6 +177,13 @@ def microbench(args, torch, synth, llma):
     slots = list(range(B))
     pend = [100 + b for b in slots]
     wbytes = 2 * cfg.streamed_params
+    # one plain 256 MiB device copy: calibrates FETCH_SIZE / WRITE_SIZE when the run is under counter collection
+    cal_src = torch.ones(256 * 1024 * 1024 // 4, dtype=torch.float32, device="cuda")
+    cal_dst = torch.empty_like(cal_src)
+    torch.cuda.synchronize()
+    cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
 
     def restore():
