@@ -711,10 +711,6 @@ __global__ __launch_bounds__(WV * 64, (FT * (EPI == EPI_SWIGLU ? 2 : 1) >= 4 ? 1
     // The weights come straight from HBM, whose latency under load (2 us and more) is several chunks
     // of MFMA work, so they are requested WD - 1 k-steps ahead into a ring of WD register sets; the loop
     // below is unrolled over one turn of the ring (WD / KC chunks), which gives every set and both
-    // activation staging arrays one fixed role per call site.
-    // The weights come straight from HBM, whose latency under load (2 us and more) is several chunks
-    // of MFMA work, so they are requested WD - 1 k-steps ahead into a ring of WD register sets; the loop
-    // below is unrolled over one turn of the ring (WD / KC chunks), which gives every set and both
     // activation staging arrays one fixed role per call site (one body taking either role made the
     // compiler copy registers between the roles every chunk, behind a wait for all loads in flight).
     // A wave's loads complete in the order it issued them, so an activation block (an L2 hit) waits
@@ -994,7 +990,7 @@ __device__ __forceinline__ void attn_chunk_body(const AttnArgs &a, float (&sm)[4
     // K and V blocks of the wave's 32 positions: issued before the sequence length is known (any
     // position below max_seq lies inside the cache allocation; unused blocks are simply dropped)
     u32x4 ka[2][KSTEPS], va[DT];
-        u32x2 kb[2][KSTEPS], vb[DT];                                 // lo planes: one byte per element
+    u32x2 kb[2][KSTEPS], vb[DT];                     // lo planes: one byte per element
     {
         const bf16_t *kh = (const bf16_t *)a.Khi + head_base; const uint8_t *kl = (const uint8_t *)a.Klo + head_base;
         const bf16_t *vh = (const bf16_t *)a.Vhi + head_base; const uint8_t *vl = (const uint8_t *)a.Vlo + head_base;
@@ -1236,7 +1232,7 @@ __global__ __launch_bounds__(256, 2) void attn_walk_bf16_kernel(AttnArgs a) {
         const bool active = key0 < kv_len;                           // uniform for the wave
         const bool use_lo = KVS && c >= c_lo;                        // uniform for the workgroup
         u32x4 ka[2][KSTEPS], va[DT];
-        u32x2 kb[2][KSTEPS], vb[DT];                                 // lo planes: one byte per element
+        u32x2 kb[2][KSTEPS], vb[DT];                     // lo planes: one byte per element
         if (active) {
 #pragma unroll
             for (int t = 0; t < 2; ++t)
@@ -1455,7 +1451,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         const int key0 = c * ATTN_CHUNK + wave * 32;
         if (key0 >= kv_len) return;                                  // uniform for the wave: no row sees these positions
         u32x4 ka[2][KSTEPS], va[DT];
-        u32x2 kb[2][KSTEPS], vb[DT];                                 // lo planes: one byte per element
+        u32x2 kb[2][KSTEPS], vb[DT];                     // lo planes: one byte per element
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
