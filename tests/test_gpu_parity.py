@@ -137,6 +137,50 @@ def test_verify_step_logits_and_state(llma, cfg):
 MINIODD = synth.ModelCfg("miniodd", 2, 192, 3, 64, 416, 1024, "bf16")
 
 
+def test_long_prompt_in_several_passes_against_oracle(llma):
+    """A 2300-token prompt goes through the model in more than one prompt pass -- as one call (2048 +
+    251 rows inside the library), as two calls (700 rows, then 1599 on top of them) and as a 30-row
+    piece (decoding-step kernels) followed by the rest -- so the prompt-pass attention also walks
+    over positions cached by an earlier pass.  After each, one verification step with k = 8 (five
+    right drafts, then wrong ones): logits of all nine rows, accepted count, next token and cache
+    length against the oracle, which was fed the prompt in one piece."""
+    cfg = MINI128
+    w = synth.make_weights(cfg, 55, gain_jitter=0.3)
+    om = OracleModel(cfg, w)
+    prompt = synth.uniform_tokens(21, 3, 2300, cfg.vocab)
+    cap = 2400
+    cache = om.new_cache(cap)
+    om.forward(prompt[:-1], cache, 0)
+    T, pending = len(prompt) - 1, int(prompt[-1])
+    good, tok = [], pending
+    for j in range(8):                                   # the oracle's own continuation = right drafts
+        tok = int(argmax_tokens(om.forward([tok], cache, T + j))[0])
+        good.append(tok)
+    draft = good[:5] + [(g + 1) % cfg.vocab for g in good[5:]]
+    want = om.forward([pending] + draft, cache, T)       # (rows T.. are rewritten: the probe above is gone)
+    o = argmax_tokens(want)
+    a = 0
+    while a < 8 and o[a] == draft[a]:
+        a += 1
+    assert a >= 5
+    atol, rtol = tol(cfg)
+    tie = any(top2_gap(want[j]) <= atol + rtol * abs(want[j].max()) for j in range(a + 1))
+    for name, cuts in (("one call", []), ("700 + 1599 rows", [700]), ("30 rows + the rest", [30])):
+        ctx = llma.Context(cfg, w, max_seq=cap, max_batch=1, max_k=8)
+        ctx.enable_logits_dump(9)
+        lo = 0
+        for c in cuts + [len(prompt) - 1]:
+            ctx.prefill(prompt[lo:c + 1])                # rows lo .. c - 1; prompt[c] becomes the pending token
+            lo = c
+        assert ctx.get_state() == (T, pending), name
+        na, nxt, emitted = ctx.verify_step(draft)
+        assert_logits_close(ctx.logits(9), want, cfg, name)
+        if not tie:
+            assert (na, nxt, emitted) == (a, int(o[a]), [int(t) for t in o[:a + 1]]), name
+        assert ctx.get_state() == (T + na + 1, nxt), name
+        ctx.close()
+
+
 def test_prompt_pass_and_steps_with_odd_k_step_counts(llma):
     """d_ffn = 416 gives the down projection 13 MFMA k-steps (d_model = 192: 6): the prompt-pass GEMM's
     last two-step chunk is half empty, the decoding GEMM's 8 K slices have 1 or 2 steps.  A 150-token prompt
