@@ -513,6 +513,54 @@ def test_argument_errors_leave_context_unchanged(llma):
     ctx.close()
 
 
+def test_steps_and_generation_up_to_the_last_cache_position(llma):
+    """A cache of 200 positions (not a whole number of 128-position attention chunks): a k = 8 step
+    whose last row sits on position 199 -- all drafts right, so the cache ends full -- against the
+    oracle; the next step of any width is refused and changes nothing.  And a generation sized so that
+    prompt + new tokens + k is exactly the capacity, tokens and trace against the oracle."""
+    cfg = MINI64
+    w = synth.make_weights(cfg, 23, gain_jitter=0.3)
+    om = OracleModel(cfg, w)
+    prompt = synth.uniform_tokens(23, 1, 192, cfg.vocab)
+    cache = om.new_cache(200)
+    om.forward(prompt[:-1], cache, 0)
+    T, pending = 191, int(prompt[-1])
+    draft, tok = [], pending
+    for j in range(8):
+        tok = int(argmax_tokens(om.forward([tok], cache, T + j))[0])
+        draft.append(tok)
+    want = om.forward([pending] + draft, cache, T)
+    o = argmax_tokens(want)
+    atol, rtol = tol(cfg)
+    tie = any(top2_gap(want[j]) <= atol + rtol * abs(want[j].max()) for j in range(9))
+    ctx = llma.Context(cfg, w, max_seq=200, max_batch=1, max_k=8)
+    ctx.enable_logits_dump(9)
+    ctx.prefill(prompt)
+    na, nxt, emitted = ctx.verify_step(draft)
+    assert_logits_close(ctx.logits(9), want, cfg, "step that ends on the last position")
+    if not tie:
+        assert (na, nxt, emitted) == (8, int(o[8]), [int(t) for t in o])
+        assert ctx.get_state() == (200, int(o[8]))
+        for d in ([], [1], draft):
+            with pytest.raises(llma.LlmaError) as e:
+                ctx.verify_step(d)
+            assert e.value.code == llma.LLMA_E_RANGE and ctx.get_state() == (200, int(o[8]))
+    ctx.close()
+
+    cfg = synth.TINY
+    w = synth.make_weights(cfg, 6)
+    om = OracleModel(cfg, w)
+    prompt = synth.uniform_tokens(6, 1, 20, cfg.vocab).tolist()
+    y = greedy_decode(CachedLLM(om, prompt, 64), 40)
+    docs = [y[4:30]]
+    yo, to = llma_decode(CachedLLM(om, prompt, 64), docs, 1, 4, 40)
+    assert yo == y
+    ctx = llma.Context(cfg, w, max_seq=64, max_batch=1, max_k=4)               # 20 + 40 + 4 = 64
+    g, t = ctx.generate(prompt, np.asarray(docs[0], dtype=np.int32), np.asarray([0, len(docs[0])], dtype=np.int32), 1, 4, 40)
+    assert g.tolist() == yo and t == to
+    ctx.close()
+
+
 def test_step_graphs_of_prompt_passes_with_256_rows_apart(llma):
     """Captured step graphs are looked up by (kind, sequences, rows, attention chunks, slot).  Two prompt
     passes whose row counts differ by 256 -- 100 rows on top of 256 cached positions and 356 rows on an
