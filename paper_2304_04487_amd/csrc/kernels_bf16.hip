@@ -349,7 +349,15 @@ __global__ __launch_bounds__((TileKShape<NT, FT>::MAX_THREADS)) void gemm_tilek_
     // slice boundaries floor(KSp * slice / S); S is 8 or 16 (a shift; a 64-bit division here costs
     // a few hundred instructions before the kernel's first load)
     const int s_sh = 31 - __builtin_clz(S);
-    int ks1 = 0;                                   // end of the K slice being streamed
+    int ks0 = 0, ks1 = 0, turn = 0;                // the K slice being streamed, and where in it the walk starts
+    // If every workgroup walked its slices from their first k-step, the whole chip would at any moment
+    // read the blocks of the same few k-steps of every tile -- addresses a fixed stride apart, which
+    // fall on few memory channels.  So the walk over a slice starts `turn` k-steps in and wraps around
+    // (QKV 18.9 -> 18.4 us, down 18.9 -> 17.9 us per launch at the 7B shapes).  The start is a
+    // function of the tile's group of 12 -- the same for 1, 2, 3 or 4 tiles per workgroup -- and of the
+    // slice length, so a tile's sums are added in an order that no launch parameter changes.
+    const int turn_grp = task0 / 12;
+    auto k_turn = [&](int len) { return len > 1 ? (turn_grp * 5) % len : 0; };
     float *rstd_s = (float *)(red + (size_t)S * AT * NT * 64);
 
     const u32x4 *wp[AT];
@@ -369,7 +377,8 @@ __global__ __launch_bounds__((TileKShape<NT, FT>::MAX_THREADS)) void gemm_tilek_
         if (k_lo < k_hi) {
 #pragma unroll
             for (int u = 0; u < UB; ++u) {
-                const int k = k_lo + u < k_hi ? k_lo + u : k_hi - 1;
+                int k = (k_lo + u < k_hi ? k_lo + u : k_hi - 1) + k_turn(k_hi - k_lo);
+                k = k >= k_hi ? k - (k_hi - k_lo) : k;
 #pragma unroll
                 for (int i = 0; i < AT; ++i) avA[i][u] = __builtin_nontemporal_load(wp[i] + (size_t)k * 64);
             }
@@ -386,7 +395,8 @@ __global__ __launch_bounds__((TileKShape<NT, FT>::MAX_THREADS)) void gemm_tilek_
 #pragma unroll
         for (int u = 0; u < UB; ++u) {
             int k = ks + u;
-            k = k < ks1 ? k : ks1 - 1;
+            k = (k < ks1 ? k : ks1 - 1) + turn;
+            k = k >= ks1 ? k - (ks1 - ks0) : k;
             if (weights)
 #pragma unroll
             for (int i = 0; i < AT; ++i) av[i][u] = __builtin_nontemporal_load(wp[i] + (size_t)k * 64);
@@ -418,6 +428,7 @@ __global__ __launch_bounds__((TileKShape<NT, FT>::MAX_THREADS)) void gemm_tilek_
     int slice = wave * SL;
     int ks = (KSp * slice) >> s_sh;
     ks1 = (KSp * (slice + 1)) >> s_sh;
+    ks0 = ks; turn = k_turn(ks1 - ks0);
     if (ks < ks1) issue(ks, avA, bvA, NT > 1);      // (one row tile: the weights are already on their way)
     // epilogue inputs and rstd while the first batch is in flight
     EpiIn<NT> in;
@@ -455,6 +466,7 @@ __global__ __launch_bounds__((TileKShape<NT, FT>::MAX_THREADS)) void gemm_tilek_
             slice = wave * SL + sl;
             ks = (KSp * slice) >> s_sh;
             ks1 = (KSp * (slice + 1)) >> s_sh;
+            ks0 = ks; turn = k_turn(ks1 - ks0);
             if (ks < ks1) issue(ks, avA, bvA);
         }
 #pragma unroll
